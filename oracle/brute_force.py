@@ -1,0 +1,59 @@
+"""Pure-Python brute force of the SparQ step for ONE head on tiny inputs.
+
+Test infrastructure only.  It exists to pin the C oracle to something that is not
+itself: lists of Python floats, full sorts, math.fsum, no numpy arithmetic, written
+directly from Section 3 (Eqs. 1, 4-8) and Section 4 (Steps 1-3).
+"""
+import math
+
+
+def softmax(xs):
+    top = max(xs)
+    es = [math.exp(x - top) for x in xs]
+    tot = math.fsum(es)
+    return [e / tot for e in es]
+
+
+def dense(q, K, V):
+    """Eq. (1)."""
+    d_h = len(q)
+    s = softmax([math.fsum(q[c] * row[c] for c in range(d_h)) / math.sqrt(d_h) for row in K])
+    return [math.fsum(s[i] * V[i][c] for i in range(len(K))) for c in range(d_h)]
+
+
+def top(values, count):
+    """Indices of the `count` largest values, ties to the lower index, ascending."""
+    order = sorted(range(len(values)), key=lambda i: (-values[i], i))
+    return sorted(order[:count])
+
+
+def sparq(q, K, V, r, k, realloc=True):
+    """Steps 1-3 for one query head.  q: [d_h], K, V: [S][d_h] (lists of floats)."""
+    d_h, S = len(q), len(K)
+    k = min(k, S)
+    # Step 1
+    i1 = top([abs(x) for x in q], r)
+    l1_all = math.fsum(abs(x) for x in q)
+    l1_sel = math.fsum(abs(q[c]) for c in i1)
+    tau = math.sqrt(d_h * l1_sel / l1_all) if l1_all > 0 else math.sqrt(d_h)
+    z = [math.fsum(q[c] * K[i][c] for c in i1) / tau for i in range(S)]
+    s_hat = softmax(z)
+    # Step 2
+    i2 = top(s_hat, k)   # the paper's literal rule: top-k of the softmax output
+    sub = softmax([math.fsum(q[c] * K[i][c] for c in range(d_h)) / math.sqrt(d_h) for i in i2])
+    y3 = [math.fsum(sub[n] * V[i][c] for n, i in enumerate(i2)) for c in range(d_h)]
+    # Step 3
+    alpha = math.fsum(s_hat[i] for i in i2)
+    v_bar = [math.fsum(V[i][c] for i in range(S)) / S for c in range(d_h)]
+    y = [alpha * y3[c] + (1 - alpha) * v_bar[c] for c in range(d_h)] if realloc else y3
+    return dict(i1=i1, tau=tau, z=z, s_hat=s_hat, i2=i2, alpha=alpha, y=y, y3=y3, v_bar=v_bar)
+
+
+def sparse_v_reallocation(q, K, V, k):
+    """Eq. (4): (s o m_s) V + (1 - s.m_s) v_bar with the exact scores s."""
+    d_h, S = len(q), len(K)
+    s = softmax([math.fsum(q[c] * row[c] for c in range(d_h)) / math.sqrt(d_h) for row in K])
+    keep = top(s, min(k, S))
+    v_bar = [math.fsum(V[i][c] for i in range(S)) / S for c in range(d_h)]
+    mass = math.fsum(s[i] for i in keep)
+    return [math.fsum(s[i] * V[i][c] for i in keep) + (1 - mass) * v_bar[c] for c in range(d_h)]
