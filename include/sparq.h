@@ -1,0 +1,148 @@
+/*
+ * libsparq: SparQ Attention single-token decode step for one MI355X (gfx950).
+ *
+ * C ABI.  Every buffer named "device" is caller-owned device memory; the library
+ * never allocates, frees or synchronises (the one exception, sparq_async_error, says
+ * so).  All work is enqueued on the caller's HIP stream (`hip_stream` is a
+ * hipStream_t passed as void*; NULL is the default stream) and is complete when the
+ * stream reaches that point.  Functions return a sparq_status; nothing throws.
+ *
+ * Notation follows the paper: B sequences, H query heads, H_kv key/value heads
+ * (g = H / H_kv query heads share a KV head), head dimension d_h, S_b cached rows in
+ * sequence b, r query components kept in Step 1, k positions kept in Step 2.
+ *
+ * Cache layout (Section 6 and Appendix F, "Storing K twice": the key cache is kept in
+ * both a d_h-contiguous and an S-contiguous layout so that either axis can be
+ * gathered with contiguous reads):
+ *   K      [B, H_kv, S_max, d_h]   16-bit, d_h-contiguous   (Step 2 gathers rows)
+ *   Kt     [B, H_kv, d_h, S_max]   16-bit, S-contiguous copy of K (Step 1 reads r rows)
+ *   V      [B, H_kv, S_max, d_h]   16-bit
+ *   v_mean [B, H_kv, d_h]          fp32 running mean of V[b, h, 0:S_b, :]
+ *                                  (Section 3, "Mean value reallocation")
+ *   seq_lens [B]                   int32, S_b
+ * S_max must be a multiple of 64 and every pointer 16-byte aligned.  d_h is 64, 128 or
+ * 256.  Rows at positions >= S_b are never read.
+ */
+#ifndef SPARQ_H
+#define SPARQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SPARQ_OK = 0,
+  SPARQ_EINVAL = -1,       /* null / misaligned pointer, inconsistent shape */
+  SPARQ_EUNSUPPORTED = -2, /* valid request this build has no kernel for */
+  SPARQ_EWORKSPACE = -3,   /* workspace missing or smaller than sparq_workspace_bytes */
+  SPARQ_ELAUNCH = -4       /* the HIP runtime refused the launch */
+} sparq_status;
+
+typedef enum { SPARQ_F16 = 0, SPARQ_BF16 = 1 } sparq_dtype;
+
+enum {
+  /* y = y3: skip the blend of Step 3 (Section 4 omits it for grouped-query models) */
+  SPARQ_FLAG_NO_REALLOC = 1u << 0,
+  /* one channel set and one position set per KV head from group sums (Section 4,
+   * "Grouped query attention").  Not built yet: returns SPARQ_EUNSUPPORTED.  The default
+   * treats every query head independently over its shared KV head. */
+  SPARQ_FLAG_GQA_SHARED = 1u << 1
+};
+
+/* bits of the device-side error word (sparq_async_error) */
+enum {
+  SPARQ_ERR_APPEND_FULL = 1,   /* an append would pass S_max: that sequence was skipped */
+  SPARQ_ERR_EMPTY_SEQ = 2,     /* decode of a sequence with S_b = 0: zeros written */
+  SPARQ_ERR_IDX_TRUNCATED = 4, /* min(k_b, S_b) exceeded idx_stride: idx_out truncated */
+  SPARQ_ERR_BAD_SEQ_LEN = 8    /* seq_lens[b] outside [0, S_max]: clamped */
+};
+
+typedef struct {
+  int32_t B, H, H_kv, S_max, d_h;
+  int32_t r;      /* 1 <= r <= d_h */
+  int32_t k;      /* >= 1; clamped per sequence to S_b */
+  int32_t dtype;  /* sparq_dtype of K, Kt, V, q and out */
+  uint32_t flags;
+} sparq_shape;
+
+typedef struct {
+  void* K;           /* device */
+  void* Kt;          /* device */
+  void* V;           /* device */
+  float* v_mean;     /* device */
+  int32_t* seq_lens; /* device */
+} sparq_cache;
+
+/* Bytes of device workspace the calls below need for this shape (>= 256).  The first word
+ * of the workspace is the error word; sparq_workspace_init zeroes it. */
+int sparq_workspace_bytes(const sparq_shape* shape, size_t* out_bytes);
+
+/* Enqueue a clear of the workspace header.  Call once after allocating the workspace. */
+int sparq_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Append rows to the cache and keep Kt and v_mean in step (the "4 d_h" term of the SparQ
+ * transfer equation in Section 4: write k and v, read and write the mean value vector;
+ * the second, non-contiguous key write is the one Appendix F describes).
+ *   k_new, v_new   device [B, H_kv, n_new, d_h], cache dtype
+ *   n_new          rows per sequence in k_new / v_new (>= 1)
+ *   n_new_per_seq  device [B] or NULL: sequence b appends only its first
+ *                  n_new_per_seq[b] rows (0..n_new); NULL appends n_new everywhere
+ * For sequence b with n rows: rows land at positions S_b..S_b+n-1 of K and V and in the
+ * matching columns of Kt, v_mean becomes the mean of the S_b+n value rows, seq_lens[b]
+ * += n.  If S_b + n > S_max the sequence is left untouched and SPARQ_ERR_APPEND_FULL is
+ * raised in the error word.  The only call that mutates the cache.
+ */
+int sparq_kv_append(const sparq_shape* shape, const sparq_cache* cache, const void* k_new,
+                    const void* v_new, int32_t n_new, const int32_t* n_new_per_seq,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * One SparQ decode step for all B x H heads (Section 4, Steps 1-3; Section 3 Eqs. 5-8).
+ * Per query head, over the rows 0..S_b-1 of its KV head:
+ *   Step 1  i1 = the r largest |q_j| (ties to the lower j);
+ *           tau = sqrt(d_h * sum_{j in i1}|q_j| / sum_j |q_j|)  (sqrt(d_h) if q = 0);
+ *           z_i = sum_{j in i1} q_j K[i,j] / tau,  s_hat = softmax(z)
+ *   Step 2  i2 = the min(k_b, S_b) positions of largest z (ties to the lower i);
+ *           y3 = softmax(q K[i2]^T / sqrt(d_h)) V[i2]
+ *   Step 3  alpha = sum_{i in i2} s_hat_i;  y = alpha y3 + (1 - alpha) v_mean
+ * Arithmetic is fp32 on the 16-bit inputs; `out` is rounded to nearest-even.
+ *   q          device [B, H, d_h]
+ *   k_per_seq  device [B] or NULL; k_per_seq[b] replaces shape.k for sequence b
+ *   out        device [B, H, d_h], cache dtype
+ *   alpha_out  device [B, H] fp32 or NULL
+ *   idx_out    device [B, H, idx_stride] int32 or NULL: i2 ascending, padded with -1
+ *   chan_out   device [B, H, r] int32 or NULL: i1 ascending
+ * Reads the cache, writes only the outputs and the error word.
+ */
+int sparq_decode(const sparq_shape* shape, const sparq_cache* cache, const void* q,
+                 const int32_t* k_per_seq, void* out, float* alpha_out, int32_t* idx_out,
+                 int32_t idx_stride, int32_t* chan_out, void* workspace,
+                 size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Dense single-query attention y = softmax(q K^T / sqrt(d_h)) V over rows 0..S_b-1
+ * (Section 3, Eq. 1): the in-library comparison.  Reads K and V once per KV head for
+ * all g query heads of the group.  Uses the workspace for split-sequence partials.
+ *   q, out  device [B, H, d_h], cache dtype
+ */
+int dense_decode(const sparq_shape* shape, const sparq_cache* cache, const void* q, void* out,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Copy the device error word to *host_flag, clear it on the device, and WAIT for the
+ * stream (this call synchronises). */
+int sparq_async_error(void* workspace, int32_t* host_flag, void* hip_stream);
+
+/* Plain device-to-device copy of n_bytes (multiple of 16) by a grid-stride kernel: the
+ * known-size copy used to calibrate HBM counters and to measure the attainable rate. */
+int sparq_copy_probe(void* dst, const void* src, size_t n_bytes, void* hip_stream);
+
+const char* sparq_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARQ_H */

@@ -1,0 +1,172 @@
+// Cache maintenance: append key/value rows, keep the S-contiguous key copy and the running
+// mean value vector in step (Section 3 "Mean value reallocation"; Appendix F "Storing K twice").
+#include "common.h"
+#include "params.h"
+
+namespace sparq {
+
+namespace {
+
+// ---- one row per sequence: the per-token path of the decode loop ----
+// One workgroup per sequence so that seq_lens[b] is read by everyone before it is bumped.
+// A thread moves one 16-byte chunk (8 channels) of one KV head at a time.
+template <class T>
+__global__ __launch_bounds__(512) void append_one_row(const AppendArgs a) {
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int S = a.seq_lens[b];
+  int n = a.n_new_per_seq ? a.n_new_per_seq[b] : 1;
+  n = n < 0 ? 0 : (n > 1 ? 1 : n);
+  if (n == 0) return;
+  if (S < 0 || S + 1 > a.S_max) {
+    if (tid == 0) atomicOr(a.err, 1);
+    return;
+  }
+  const int cpr = a.d_h / 8;                  // 16-byte chunks per row
+  const int n_chunks = a.H_kv * cpr;
+  const float inv = 1.0f / (float)(S + 1);
+  for (int c = tid; c < n_chunks; c += 512) {
+    const int hk = c / cpr, j0 = (c - hk * cpr) * 8;
+    const size_t head = (size_t)b * a.H_kv + hk;
+    const uint4 kc = load16(reinterpret_cast<const uint16_t*>(a.k_new) + head * a.d_h + j0);
+    const uint4 vc = load16(reinterpret_cast<const uint16_t*>(a.v_new) + head * a.d_h + j0);
+    uint16_t* Krow = reinterpret_cast<uint16_t*>(a.K) + (head * a.S_max + S) * a.d_h + j0;
+    uint16_t* Vrow = reinterpret_cast<uint16_t*>(a.V) + (head * a.S_max + S) * a.d_h + j0;
+    *reinterpret_cast<uint4*>(Krow) = kc;
+    *reinterpret_cast<uint4*>(Vrow) = vc;
+    // the same 8 key elements go down column S of the S-contiguous copy (2-byte stores)
+    uint16_t* Ktcol = reinterpret_cast<uint16_t*>(a.Kt) + (head * a.d_h + j0) * a.S_max + S;
+    const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      Ktcol[(size_t)e * a.S_max] = (uint16_t)((e & 1) ? (kw[e >> 1] >> 16) : (kw[e >> 1] & 0xffffu));
+    // running mean: v_mean += (v - v_mean) / (S + 1)
+    float* vm = a.v_mean + head * a.d_h + j0;
+    float4 m0 = *reinterpret_cast<float4*>(vm), m1 = *reinterpret_cast<float4*>(vm + 4);
+    float f[8];
+    unpack8<T>(vc, f);
+    m0.x += (f[0] - m0.x) * inv; m0.y += (f[1] - m0.y) * inv; m0.z += (f[2] - m0.z) * inv; m0.w += (f[3] - m0.w) * inv;
+    m1.x += (f[4] - m1.x) * inv; m1.y += (f[5] - m1.y) * inv; m1.z += (f[6] - m1.z) * inv; m1.w += (f[7] - m1.w) * inv;
+    *reinterpret_cast<float4*>(vm) = m0;
+    *reinterpret_cast<float4*>(vm + 4) = m1;
+  }
+  __syncthreads();
+  if (tid == 0) a.seq_lens[b] = S + 1;
+}
+
+// ---- many rows per sequence (prefill / cache construction) ----
+// One workgroup per (sequence, KV head); tiles of 64 positions go through LDS to be written
+// transposed; value columns are summed in fp64 and folded into the mean once.
+constexpr int BT = 256;       // threads
+constexpr int TILE = 64;      // positions per tile
+
+template <class T, int DH>
+__global__ __launch_bounds__(BT) void append_rows(const AppendArgs a) {
+  constexpr int CPR = DH / 8;            // 16-byte chunks per row
+  constexpr int RPP = BT / CPR;          // rows per pass
+  constexpr int LD = DH + 2;             // padded LDS row (elements): conflict-free column reads
+  __shared__ uint16_t tile[TILE * LD];
+  __shared__ double colsum[RPP][DH];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const size_t head = blockIdx.x;
+  const int b = (int)(head / a.H_kv);
+  const int S = a.seq_lens[b];
+  int n = a.n_new_per_seq ? a.n_new_per_seq[b] : a.n_new;
+  n = n < 0 ? 0 : (n > a.n_new ? a.n_new : n);
+  if (n == 0) return;
+  if (S < 0 || S + n > a.S_max) {
+    if (tid == 0) atomicOr(a.err, 1);
+    return;
+  }
+  const int sub = tid % CPR, prow = tid / CPR;
+  const uint16_t* ksrc = reinterpret_cast<const uint16_t*>(a.k_new) + head * a.n_new * DH;
+  const uint16_t* vsrc = reinterpret_cast<const uint16_t*>(a.v_new) + head * a.n_new * DH;
+  uint16_t* Kdst = reinterpret_cast<uint16_t*>(a.K) + (head * a.S_max + S) * DH;
+  uint16_t* Vdst = reinterpret_cast<uint16_t*>(a.V) + (head * a.S_max + S) * DH;
+  uint16_t* Ktdst = reinterpret_cast<uint16_t*>(a.Kt) + head * DH * a.S_max + S;
+  double sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int n0 = 0; n0 < n; n0 += TILE) {
+    const int rows = (n - n0) < TILE ? (n - n0) : TILE;
+    for (int rr = prow; rr < rows; rr += RPP) {
+      const size_t off = (size_t)(n0 + rr) * DH + sub * 8;
+      const uint4 kc = load16(ksrc + off), vc = load16(vsrc + off);
+      *reinterpret_cast<uint4*>(Kdst + off) = kc;
+      *reinterpret_cast<uint4*>(Vdst + off) = vc;
+      uint32_t* t32 = reinterpret_cast<uint32_t*>(tile + rr * LD + sub * 8);   // LD even: 4-byte aligned
+      t32[0] = kc.x; t32[1] = kc.y; t32[2] = kc.z; t32[3] = kc.w;
+      float f[8];
+      unpack8<T>(vc, f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum[e] += (double)f[e];
+    }
+    __syncthreads();
+    for (int j = wave; j < DH; j += BT / 64)
+      if (lane < rows) Ktdst[(size_t)j * a.S_max + n0 + lane] = tile[lane * LD + j];
+    __syncthreads();
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) colsum[prow][sub * 8 + e] = sum[e];
+  __syncthreads();
+  if (tid < DH) {
+    double tot = 0.0;
+    for (int p = 0; p < RPP; ++p) tot += colsum[p][tid];
+    float* vm = a.v_mean + head * DH + tid;
+    *vm = (float)(((double)S * (double)*vm + tot) / (double)(S + n));
+  }
+}
+
+__global__ void bump_seq_lens(const AppendArgs a) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= a.B) return;
+  const int S = a.seq_lens[b];
+  int n = a.n_new_per_seq ? a.n_new_per_seq[b] : a.n_new;
+  n = n < 0 ? 0 : (n > a.n_new ? a.n_new : n);
+  if (S >= 0 && S + n <= a.S_max) a.seq_lens[b] = S + n;
+}
+
+__global__ __launch_bounds__(256) void copy_probe(uint4* dst, const uint4* src, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ void clear_header(int32_t* w) {
+  if (threadIdx.x < kWorkspaceHeader / 4) w[threadIdx.x] = 0;
+}
+
+template <class T>
+hipError_t launch_rows(const AppendArgs& a, hipStream_t s) {
+  const dim3 grid(a.B * a.H_kv);
+  switch (a.d_h) {
+    case 64:  hipLaunchKernelGGL((append_rows<T, 64>), grid, dim3(BT), 0, s, a); break;
+    case 128: hipLaunchKernelGGL((append_rows<T, 128>), grid, dim3(BT), 0, s, a); break;
+    case 256: hipLaunchKernelGGL((append_rows<T, 256>), grid, dim3(BT), 0, s, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(bump_seq_lens, dim3((a.B + 255) / 256), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t s) {
+  if (a.n_new == 1) {
+    if (dtype == 1) hipLaunchKernelGGL(append_one_row<BF16>, dim3(a.B), dim3(512), 0, s, a);
+    else hipLaunchKernelGGL(append_one_row<F16>, dim3(a.B), dim3(512), 0, s, a);
+    return hipGetLastError();
+  }
+  return dtype == 1 ? launch_rows<BF16>(a, s) : launch_rows<F16>(a, s);
+}
+
+hipError_t launch_copy_probe(void* dst, const void* src, size_t n_bytes, hipStream_t s) {
+  hipLaunchKernelGGL(copy_probe, dim3(256 * 8), dim3(256), 0, s, reinterpret_cast<uint4*>(dst),
+                     reinterpret_cast<const uint4*>(src), n_bytes / 16);
+  return hipGetLastError();
+}
+
+hipError_t launch_clear_header(void* workspace, hipStream_t s) {
+  hipLaunchKernelGGL(clear_header, dim3(1), dim3(64), 0, s, reinterpret_cast<int32_t*>(workspace));
+  return hipGetLastError();
+}
+
+}  // namespace sparq

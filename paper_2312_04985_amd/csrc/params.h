@@ -1,0 +1,43 @@
+// Kernel argument blocks and launcher prototypes (internal to libsparq).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace sparq {
+
+constexpr int kDecodeThreads = 512;     // threads per workgroup of the fused decode kernel
+constexpr int kRadixBins = 2048;        // 11-bit digits: passes of 11, 11 and 10 bits
+constexpr int kWorkspaceHeader = 256;   // bytes; word 0 is the error word
+
+struct DecodeArgs {
+  const void* K; const void* Kt; const void* V; const float* v_mean; const int32_t* seq_lens;
+  const void* q; const int32_t* k_per_seq;
+  void* out; float* alpha_out; int32_t* idx_out; int32_t* chan_out; int32_t* err;
+  int32_t B, H, H_kv, S_max, d_h, r, k, idx_stride;
+  uint32_t flags;
+};
+
+struct AppendArgs {
+  void* K; void* Kt; void* V; float* v_mean; int32_t* seq_lens;
+  const void* k_new; const void* v_new; const int32_t* n_new_per_seq; int32_t* err;
+  int32_t B, H_kv, S_max, d_h, n_new;
+};
+
+struct DenseArgs {
+  const void* K; const void* V; const int32_t* seq_lens; const void* q; void* out;
+  float* partials;   // [B*H, n_split, d_h + 2]
+  int32_t* err;
+  int32_t B, H, H_kv, S_max, d_h, n_split, rows_per_split;
+};
+
+// LDS bytes the fused decode kernel needs for a cache of S_max rows and head dimension d_h
+size_t decode_lds_bytes(int S_max, int d_h);
+
+hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s);
+hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t s);
+hipError_t launch_dense(const DenseArgs& a, int dtype, hipStream_t s);
+hipError_t launch_copy_probe(void* dst, const void* src, size_t n_bytes, hipStream_t s);
+hipError_t launch_clear_header(void* workspace, hipStream_t s);
+
+}  // namespace sparq

@@ -1,0 +1,81 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function the
+header declares, and refuses bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2312_04985_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000      # 16-byte aligned, never dereferenced: validation fails first
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sparq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"^(?:int|const char\*)\s+(\w+)\s*\(", text, flags=re.M)))
+
+
+def test_library_exports_every_declared_function():
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS) and len(names) >= 8
+    lib = B.load()
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings():
+    assert B.status_string(0) == "ok"
+    assert len({B.status_string(s) for s in (0, -1, -2, -3, -4, -99)}) == 6
+
+
+def shape(**kw):
+    d = dict(B=2, H=4, H_kv=2, S_max=128, d_h=128, r=16, k=8, dtype=0, flags=0)
+    d.update(kw)
+    return B.SparqShape(*[d[f] for f, _ in B.SparqShape._fields_])
+
+
+def test_workspace_bytes_and_shape_validation():
+    need = B.sparq_workspace_bytes(shape())
+    assert need >= 256 + 2 * 4 * (128 + 2) * 4
+    assert B.sparq_workspace_bytes(shape(S_max=32768, B=1, H=32, H_kv=8)) > need
+    for bad, code in [(dict(S_max=100), B.SPARQ_EINVAL), (dict(H=5), B.SPARQ_EINVAL), (dict(r=0), B.SPARQ_EINVAL),
+                      (dict(r=129), B.SPARQ_EINVAL), (dict(k=0), B.SPARQ_EINVAL), (dict(dtype=2), B.SPARQ_EINVAL),
+                      (dict(flags=64), B.SPARQ_EINVAL), (dict(B=0), B.SPARQ_EINVAL), (dict(d_h=80, r=16), B.SPARQ_EUNSUPPORTED)]:
+        with pytest.raises(B.SparqError) as e:
+            B.sparq_workspace_bytes(shape(**bad))
+        assert e.value.status == code, bad
+
+
+def call_decode(sh, cache, q=FAKE, out=FAKE, ws=FAKE, ws_bytes=1 << 30, idx=None, idx_stride=0):
+    return B.load().sparq_decode(ctypes.byref(sh), ctypes.byref(cache), q, None, out, None, idx, idx_stride, None, ws, ws_bytes, None)
+
+
+def test_bad_pointers_and_workspace_are_refused_before_any_launch():
+    lib = B.load()
+    good = B.SparqCache(FAKE, FAKE, FAKE, FAKE, FAKE)
+    sh = shape()
+    assert call_decode(sh, B.SparqCache(None, FAKE, FAKE, FAKE, FAKE)) == B.SPARQ_EINVAL
+    assert call_decode(sh, B.SparqCache(FAKE, FAKE + 2, FAKE, FAKE, FAKE)) == B.SPARQ_EINVAL
+    assert call_decode(sh, good, q=None) == B.SPARQ_EINVAL
+    assert call_decode(sh, good, out=FAKE + 8) == B.SPARQ_EINVAL
+    assert call_decode(sh, good, ws=None) == B.SPARQ_EWORKSPACE
+    assert call_decode(sh, good, ws_bytes=256) == B.SPARQ_EWORKSPACE
+    assert call_decode(sh, good, idx=FAKE, idx_stride=0) == B.SPARQ_EINVAL
+    assert lib.dense_decode(ctypes.byref(sh), ctypes.byref(good), FAKE, FAKE, FAKE, 64, None) == B.SPARQ_EWORKSPACE
+    assert lib.dense_decode(ctypes.byref(sh), ctypes.byref(good), None, FAKE, FAKE, 1 << 30, None) == B.SPARQ_EINVAL
+    assert lib.sparq_kv_append(ctypes.byref(sh), ctypes.byref(good), FAKE, FAKE, 0, None, FAKE, 1 << 30, None) == B.SPARQ_EINVAL
+    assert lib.sparq_kv_append(ctypes.byref(sh), ctypes.byref(good), FAKE, None, 1, None, FAKE, 1 << 30, None) == B.SPARQ_EINVAL
+    assert lib.sparq_kv_append(ctypes.byref(sh), ctypes.byref(good), FAKE, FAKE, 129, None, FAKE, 1 << 30, None) == B.SPARQ_EINVAL
+    assert lib.sparq_kv_append(ctypes.byref(sh), ctypes.byref(good), FAKE, FAKE, 1, None, FAKE, 16, None) == B.SPARQ_EWORKSPACE
+    assert lib.sparq_copy_probe(FAKE, FAKE, 24, None) == B.SPARQ_EINVAL
+    assert lib.sparq_workspace_init(None, 4096, None) == B.SPARQ_EWORKSPACE
+    assert lib.sparq_async_error(None, None, None) == B.SPARQ_EINVAL
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        B.make_cache(torch.zeros(4), torch.zeros(4), torch.zeros(4), torch.zeros(4), torch.zeros(4, dtype=torch.int32))
