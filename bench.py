@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the SparQ decode step on one MI355X.
+
+A "step" is one pass of the whole hot path for one new token of every sequence in the batch:
+sparq_kv_append (write k, v, the second key layout, update the mean value vector) followed by
+sparq_decode (Steps 1-3 of Section 4 for all B x H heads).  Inputs are synthetic, seeded, shaped
+like the named workload and resident in HBM before the timed region.  To keep the timed steps
+out of the 256 MB last-level cache, the run rotates over several identical cache copies and a
+pool of queries.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2_llama2_7b")
+    ap.add_argument("--copies", type=int, default=0, help="cache copies to rotate over (0 = enough for > 1 GB touched)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    return ap.parse_args()
+
+
+def traffic_from_profile(workload: str):
+    """HBM bytes per sparq_decode launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+    read from the committed summary if there is one for this workload."""
+    path = os.path.join(ROOT, "profiles", f"sparq_decode_{workload}_pmc.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(units shard over batch and KV heads with no exchange; see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU: libsparq has no CPU path", file=sys.stderr)
+        sys.exit(1)
+    from paper_2312_04985_amd import binding as B
+    from paper_2312_04985_amd import traffic as T
+    from paper_2312_04985_amd import workloads as W
+    from paper_2312_04985_amd.cache import DecodeCache
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    w = W.CONFIGS[args.workload]
+    K, Wm = args.steps, args.warmup
+    seq0 = W.draw_seq_lens(w)                       # lengths seen by the first timed decode
+    kps = W.k_per_seq(w, seq0)
+    e = 2
+    step_bytes0 = T.sparq_decode_bytes(seq0.tolist(), w.H, w.d_h, w.r, w.k, e, None if kps is None else kps.tolist())
+    copies = args.copies or max(2, -(-(1 << 30) // step_bytes0["total"]))
+    per_copy = -(-max(K, Wm) // copies) + 1          # appends one copy receives in one pass
+    S_max = W.round_up(int(seq0.max()) + per_copy, 64)
+
+    # ---- build the caches through the library (bulk append of S_b - 1 rows) ----
+    K_src, V_src = W.draw_kv(w, dev, n_rows=int(seq0.max()))
+    caches = []
+    for _ in range(copies):
+        c = DecodeCache(w.B, w.H, w.H_kv, S_max, w.d_h, w.r, w.k, w.torch_dtype, device=dev)
+        c.append(K_src, V_src, (seq0 - 1).to(dev))
+        caches.append(c)
+    torch.cuda.synchronize()
+    snap = [(c.v_mean.clone(), c.seq_lens.clone()) for c in caches]
+    n_pool = 16
+    q_pool = W.draw_queries(w, K_src, seq0, n=n_pool)
+    kn_pool, vn_pool = W.draw_kv(W.scaled(w, seed=w.seed + 1000), dev, n_rows=n_pool)
+    kn_pool = kn_pool.transpose(0, 2).transpose(1, 2).contiguous()     # [n_pool, B, H_kv, d_h]
+    vn_pool = vn_pool.transpose(0, 2).transpose(1, 2).contiguous()
+    kps_dev = None if kps is None else kps.to(dev)
+    outs = [torch.empty((w.B, w.H, w.d_h), dtype=w.torch_dtype, device=dev) for _ in range(2)]
+
+    lib = B.load()
+    stream = torch.cuda.current_stream().cuda_stream
+    vp = ctypes.c_void_p
+
+    def ptr(t):
+        return None if t is None else vp(t.data_ptr())
+
+    # pre-marshalled argument tuples: the timed loops only call into the C ABI
+    app_args, dec_args, den_args = [], [], []
+    for i in range(copies * n_pool):
+        c, j = caches[i % copies], i % n_pool
+        ws, wsb = ptr(c.workspace), c.workspace.numel()
+        app_args.append((ctypes.byref(c.shape), ctypes.byref(c.cache), ptr(kn_pool[j]), ptr(vn_pool[j]), 1, None, ws, wsb, stream))
+        dec_args.append((ctypes.byref(c.shape), ctypes.byref(c.cache), ptr(q_pool[j]), ptr(kps_dev), ptr(outs[i % 2]),
+                         None, None, 0, None, ws, wsb, stream))
+        den_args.append((ctypes.byref(c.shape), ctypes.byref(c.cache), ptr(q_pool[j]), ptr(outs[i % 2]), ws, wsb, stream))
+    n_args = len(app_args)
+
+    def restore():
+        for c, (vm, sl) in zip(caches, snap):
+            c.v_mean.copy_(vm); c.seq_lens.copy_(sl)
+        torch.cuda.synchronize()
+
+    def step(i):
+        rc = lib.sparq_kv_append(*app_args[i % n_args]) or lib.sparq_decode(*dec_args[i % n_args])
+        if rc:
+            raise RuntimeError(f"libsparq call failed: {B.status_string(rc)}")
+
+    # ---- warm-up, then the timed region: exactly K steps between two device syncs ----
+    for i in range(Wm):
+        step(i)
+    restore()
+    t0 = time.perf_counter()
+    for i in range(K):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    flags = sum(c.error_flags() for c in caches)
+    if flags:
+        raise RuntimeError(f"device error word set during the timed region: {flags}")
+
+    # ---- per-launch duration of the dominant kernel (sparq_decode) with events on its stream ----
+    restore()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    for i in range(K):
+        lib.sparq_kv_append(*app_args[i % n_args])
+        ev[i][0].record()
+        lib.sparq_decode(*dec_args[i % n_args])
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    dec_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    dec_avg_ms = sum(dec_ms) / K
+
+    # appends alone (same rotation), for the record
+    restore()
+    torch.cuda.synchronize(); ta = time.perf_counter()
+    for i in range(K):
+        lib.sparq_kv_append(*app_args[i % n_args])
+    torch.cuda.synchronize(); append_ms = (time.perf_counter() - ta) * 1e3 / K
+
+    # algorithmic bytes of the decode launches of the timed pass (S grows by one row per visit of a copy)
+    tot = {"stage1": 0, "stage3": 0, "blend": 0, "total": 0}
+    for i in range(K):
+        seq_i = (seq0 + (i // copies)).tolist()
+        kk = None if kps is None else kps.tolist()
+        bts = T.sparq_decode_bytes(seq_i, w.H, w.d_h, w.r, w.k, e, kk)
+        for key in tot:
+            tot[key] += bts[key]
+    dec_bytes = tot["total"] / K
+    app_bytes = T.kv_append_bytes(w.B, w.H_kv, w.d_h, e)
+    achieved = dec_bytes / (dec_avg_ms * 1e-3) / 1e9
+
+    # ---- in-library dense decode on the same rotation ----
+    dense = {}
+    if not args.no_dense:
+        for i in range(min(Wm, 5)):
+            lib.dense_decode(*den_args[i % n_args])
+        torch.cuda.synchronize(); td = time.perf_counter()
+        nd = max(10, K // 4)
+        for i in range(nd):
+            lib.dense_decode(*den_args[i % n_args])
+        torch.cuda.synchronize(); dense_ms = (time.perf_counter() - td) * 1e3 / nd
+        dbytes = T.dense_decode_bytes(seq0.tolist(), w.H, w.H_kv, w.d_h, e)
+        dense = {"dense_ms_per_step": round(dense_ms, 4), "dense_GBps": round(dbytes / dense_ms / 1e6, 1),
+                 "dense_frac_of_peak": round(dbytes / dense_ms / 1e6 / HBM_PEAK_GBS, 4),
+                 "speedup_vs_dense": round(dense_ms / ms_per_step, 3),
+                 "transfer_ratio_dense_over_sparq": round(dbytes / (dec_bytes + app_bytes), 3)}
+
+    # ---- CPU oracle on the host cores, on a bounded sample of the same workload ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import sparq_oracle as O
+        import numpy as np
+        restore()
+        c = caches[0]
+        c.append(kn_pool[0], vn_pool[0]); torch.cuda.synchronize()
+        # sample: the first n_b sequences of the batch (all heads), sized for roughly cpu-seconds of work
+        n_b = w.B
+        Kh = W.to_codes(c.K[:n_b]); Vh = W.to_codes(c.V[:n_b]); qh = W.to_codes(q_pool[0][:n_b])
+        seq_h = c.seq_lens[:n_b].cpu().numpy(); kk = None if kps is None else kps[:n_b].numpy()
+        reps, spent = 0, 0.0
+        while spent < args.cpu_seconds and reps < 50:
+            tc = time.perf_counter()
+            ref = O.sparq_decode(Kh, Vh, qh, seq_h, r=w.r, k=w.k, dtype=w.dtype_code, k_per_seq=kk)
+            spent += time.perf_counter() - tc; reps += 1
+        cpu = {"value": round(reps / spent, 4), "unit": "decode steps/s", "cores": O.num_threads(), "kind": "oracle",
+               "sample": f"full {args.workload} batch ({n_b} sequences x {w.H} heads), {reps} repetitions of "
+                         f"oracle_sparq_decode in {spent:.1f} s (fp64, OpenMP over (sequence, KV head))"}
+        # while the data is on the host: the timed kernels' output against the oracle on sampled heads
+        got = c.decode(q_pool[0], kps_dev).float().cpu().numpy()
+        bad = float(np.abs(got[:n_b] - ref.y).max())
+        cpu["max_abs_diff_vs_gpu"] = round(bad, 6)
+
+    rec = {
+        "metric": "SparQ decode steps/s and achieved HBM GB/s (% peak) vs dense decode, 1 MI355X",
+        "value": round(1e3 / ms_per_step, 2), "unit": "decode steps/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "B": w.B, "H": w.H, "H_kv": w.H_kv, "d_h": w.d_h, "S": int(seq0.max()),
+                   "r": w.r, "k": w.k if kps is None else "ceil(S_b/%d)" % w.k_div, "cache_dtype": w.dtype,
+                   "step": "sparq_kv_append + sparq_decode", "cache_copies_rotated": copies, "q_pool": n_pool,
+                   "S_max": S_max},
+        "step_GBps": round((dec_bytes + app_bytes) / ms_per_step / 1e6, 1),
+        "step_frac_of_peak": round((dec_bytes + app_bytes) / ms_per_step / 1e6 / HBM_PEAK_GBS, 4),
+        "append_ms": round(append_ms, 5),
+        "roofline": {"kernel": "sparq_decode_fused", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic_from_profile(args.workload),
+                     "algorithmic_bytes_per_launch": int(dec_bytes), "avg_launch_ms": round(dec_avg_ms, 5),
+                     "median_launch_ms": round(dec_ms[K // 2], 5),
+                     "stage_bytes": {k2: int(v / K) for k2, v in tot.items()}},
+        "cpu_baseline": cpu,
+    }
+    rec.update(dense)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

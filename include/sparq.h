@@ -140,6 +140,10 @@ int sparq_async_error(void* workspace, int32_t* host_flag, void* hip_stream);
  * known-size copy used to calibrate HBM counters and to measure the attainable rate. */
 int sparq_copy_probe(void* dst, const void* src, size_t n_bytes, void* hip_stream);
 
+/* Plain streaming read of n_bytes (multiple of 16) by the same grid; each thread stores one
+ * folded word to `sink` (device, at least 2 MiB = 2048 workgroups x 256 threads x 4 bytes). */
+int sparq_read_probe(const void* src, size_t n_bytes, void* sink, size_t sink_bytes, void* hip_stream);
+
 const char* sparq_status_string(int status);
 
 #ifdef __cplusplus

@@ -21,7 +21,7 @@ SPARQ_ERR_APPEND_FULL, SPARQ_ERR_EMPTY_SEQ, SPARQ_ERR_IDX_TRUNCATED, SPARQ_ERR_B
 SPARQ_OK, SPARQ_EINVAL, SPARQ_EUNSUPPORTED, SPARQ_EWORKSPACE, SPARQ_ELAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ["sparq_workspace_bytes", "sparq_workspace_init", "sparq_kv_append", "sparq_decode",
-           "dense_decode", "sparq_async_error", "sparq_copy_probe", "sparq_status_string"]
+           "dense_decode", "sparq_async_error", "sparq_copy_probe", "sparq_read_probe", "sparq_status_string"]
 
 
 class SparqShape(ctypes.Structure):
@@ -62,6 +62,7 @@ def load() -> ctypes.CDLL:
     L.dense_decode.argtypes = [shp, cch, vp, vp, vp, sz, vp]
     L.sparq_async_error.argtypes = [vp, ctypes.POINTER(i32), vp]
     L.sparq_copy_probe.argtypes = [vp, vp, sz, vp]
+    L.sparq_read_probe.argtypes = [vp, sz, vp, sz, vp]
     L.sparq_status_string.argtypes = [ctypes.c_int]
     L.sparq_status_string.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -153,3 +154,8 @@ def sparq_async_error(workspace, stream=None) -> int:
 
 def sparq_copy_probe(dst, src, n_bytes: int, stream=None) -> None:
     _check("sparq_copy_probe", load().sparq_copy_probe(_dev(dst, "dst"), _dev(src, "src"), int(n_bytes), _stream(stream)))
+
+
+def sparq_read_probe(src, n_bytes: int, sink, stream=None) -> None:
+    _check("sparq_read_probe", load().sparq_read_probe(_dev(src, "src"), int(n_bytes), _dev(sink, "sink"),
+                                                       sink.numel() * sink.element_size(), _stream(stream)))

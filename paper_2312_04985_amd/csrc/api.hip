@@ -155,6 +155,12 @@ int sparq_copy_probe(void* dst, const void* src, size_t n_bytes, void* hip_strea
   return launch_copy_probe(dst, src, n_bytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
+int sparq_read_probe(const void* src, size_t n_bytes, void* sink, size_t sink_bytes, void* hip_stream) {
+  if (!src || !sink || !aligned16(src) || !aligned16(sink) || n_bytes % 16 != 0) return SPARQ_EINVAL;
+  if (sink_bytes < (size_t)kProbeBlocks * 256 * sizeof(uint32_t)) return SPARQ_EWORKSPACE;
+  return launch_read_probe(src, n_bytes, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
+}
+
 const char* sparq_status_string(int status) {
   switch (status) {
     case SPARQ_OK: return "ok";

@@ -123,9 +123,37 @@ __global__ void bump_seq_lens(const AppendArgs a) {
   if (S >= 0 && S + n <= a.S_max) a.seq_lens[b] = S + n;
 }
 
+// Both probes keep 8 independent 16-byte accesses per thread in flight.
 __global__ __launch_bounds__(256) void copy_probe(uint4* dst, const uint4* src, size_t n16) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    uint4 v[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = src[i + t * stride];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) dst[i + t * stride] = v[t];
+  }
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+// streaming read: every thread folds its 16-byte words into one and stores it, so nothing is elided
+__global__ __launch_bounds__(256) void read_probe(const uint4* src, size_t n16, uint32_t* sink) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  uint32_t acc = 0;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    uint4 v[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = src[i + t * stride];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc ^= v[t].x ^ v[t].y ^ v[t].z ^ v[t].w;
+  }
+  for (; i < n16; i += stride) {
+    const uint4 v = src[i];
+    acc ^= v.x ^ v.y ^ v.z ^ v.w;
+  }
+  sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = acc;
 }
 
 __global__ void clear_header(int32_t* w) {
@@ -159,8 +187,14 @@ hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t s) {
 }
 
 hipError_t launch_copy_probe(void* dst, const void* src, size_t n_bytes, hipStream_t s) {
-  hipLaunchKernelGGL(copy_probe, dim3(256 * 8), dim3(256), 0, s, reinterpret_cast<uint4*>(dst),
+  hipLaunchKernelGGL(copy_probe, dim3(kProbeBlocks), dim3(256), 0, s, reinterpret_cast<uint4*>(dst),
                      reinterpret_cast<const uint4*>(src), n_bytes / 16);
+  return hipGetLastError();
+}
+
+hipError_t launch_read_probe(const void* src, size_t n_bytes, void* sink, hipStream_t s) {
+  hipLaunchKernelGGL(read_probe, dim3(kProbeBlocks), dim3(256), 0, s, reinterpret_cast<const uint4*>(src),
+                     n_bytes / 16, reinterpret_cast<uint32_t*>(sink));
   return hipGetLastError();
 }
 

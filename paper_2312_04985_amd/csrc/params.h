@@ -9,6 +9,7 @@ namespace sparq {
 constexpr int kDecodeThreads = 512;     // threads per workgroup of the fused decode kernel
 constexpr int kRadixBins = 2048;        // 11-bit digits: passes of 11, 11 and 10 bits
 constexpr int kWorkspaceHeader = 256;   // bytes; word 0 is the error word
+constexpr int kProbeBlocks = 256 * 8;   // workgroups (of 256 threads) of the bandwidth probes
 
 struct DecodeArgs {
   const void* K; const void* Kt; const void* V; const float* v_mean; const int32_t* seq_lens;
@@ -38,6 +39,7 @@ hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t s);
 hipError_t launch_dense(const DenseArgs& a, int dtype, hipStream_t s);
 hipError_t launch_copy_probe(void* dst, const void* src, size_t n_bytes, hipStream_t s);
+hipError_t launch_read_probe(const void* src, size_t n_bytes, void* sink, hipStream_t s);
 hipError_t launch_clear_header(void* workspace, hipStream_t s);
 
 }  // namespace sparq

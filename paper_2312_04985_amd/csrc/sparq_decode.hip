@@ -4,7 +4,8 @@
 //   stage 0  top-r of |q| (rank by comparison on the 16-bit magnitudes), temperature (Eq. 7)
 //   stage 1  stream the r selected rows of the S-contiguous key copy, fp32 approximate logits
 //            for every cached position into LDS as order-preserving integer keys
-//   stage 2  radix select (11/11/10-bit digits, LDS histograms) of the k-th largest key,
+//   stage 2  radix select (11/11/10-bit digits, LDS histograms; the first digit is counted while
+//            stage 1 produces the keys) of the k-th largest key,
 //            ordered compaction of the selected positions (ties to the lower position),
 //            alpha = selected share of the softmax mass of the approximate logits
 //   stage 3  gather the selected K and V rows, online-softmax exact attention, blend with
@@ -21,14 +22,14 @@ constexpr int NW = NT / kWave;   // waves per workgroup
 
 struct Lds {
   uint32_t* keys;   // [S_max]   stage 1-2: keys; after compaction: selected positions
-  uint32_t* hist;   // [kRadixBins]
-  float* part;      // [NW * (DH + 2)]
+  uint32_t* hist;   // [2][kRadixBins] double-buffered digit histograms
+  float* part;      // [NW * (DH + 2)] stage-3 partials; stage 0: partial ranks (NT words)
   float* qf;        // [DH] query as fp32
   float* qs;        // [DH] selected query components, channel-ascending
   int* chan;        // [DH] selected channels, ascending
   uint32_t* mag;    // [DH] 15-bit magnitudes
   float* red;       // [32]
-  uint32_t* wcnt;   // [16]
+  uint32_t* wcnt;   // [2][NW] double-buffered wave totals of the workgroup scan
   int* ctl;         // [8]
 };
 
@@ -36,7 +37,7 @@ template <int DH>
 __device__ __forceinline__ Lds carve(uint32_t* base, int S_max) {
   Lds l;
   l.keys = base; base += S_max;
-  l.hist = base; base += kRadixBins;
+  l.hist = base; base += 2 * kRadixBins;
   l.part = reinterpret_cast<float*>(base); base += NW * (DH + 2);
   l.qf = reinterpret_cast<float*>(base); base += DH;
   l.qs = reinterpret_cast<float*>(base); base += DH;
@@ -49,29 +50,67 @@ __device__ __forceinline__ Lds carve(uint32_t* base, int S_max) {
 }
 
 // Exclusive prefix sum of v over the workgroup in thread order; *total gets the sum.
-// Two barriers; wsum must hold NW words.
+// One barrier; callers alternate `wsum` between two NW-word buffers on consecutive calls.
 __device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wsum, int lane, int wave,
                                                     uint32_t* total) {
-  uint32_t incl = wave_scan_incl(v, lane);
+  const uint32_t incl = wave_scan_incl(v);
   if (lane == kWave - 1) wsum[wave] = incl;
   __syncthreads();
   uint32_t before = 0, all = 0;
 #pragma unroll
   for (int w = 0; w < NW; ++w) {
-    uint32_t t = wsum[w];
+    const uint32_t t = wsum[w];
     if (w < wave) before += t;
     all += t;
   }
-  __syncthreads();
   *total = all;
   return before + incl - v;
 }
 
+// Histogram bins are stored swizzled so that the 32 consecutive digits a lane sums in
+// find_threshold_bin sit in 32 different rows of 64 words: lane-consecutive, conflict-free reads.
+__device__ __forceinline__ uint32_t hist_slot(uint32_t digit) { return ((digit & 31u) << 6) | (digit >> 5); }
+
+// One wave locates the digit at which the count taken from the top digit downwards reaches `need`;
+// writes {digit, how many keys of that digit are needed, keys with that digit} to ctl[0..2].
+// Two levels: lane l sums digits 32l..32l+31 and a wave scan finds the lane, then the 32 digits of
+// that lane are scanned across lanes.  Requires 1 <= need <= total count.
+__device__ __forceinline__ void find_threshold_bin(const uint32_t* hist, int need, int lane, int* ctl) {
+  uint32_t mine = 0;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) mine += hist[(i << 6) | lane];
+  const uint32_t incl = wave_scan_incl(mine);
+  const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
+  const uint32_t above = total - incl;      // keys with digits owned by higher lanes
+  const uint64_t hit = __ballot(above < (uint32_t)need && (uint32_t)need <= above + mine);
+  const int ls = hit ? __ffsll((unsigned long long)hit) - 1 : 0;
+  const uint32_t need2 = (uint32_t)need - (uint32_t)__shfl((int)above, ls);
+  // lane t < 32 takes digit 32*ls + 31 - t, so that the scan runs from the top digit down
+  const uint32_t c = lane < 32 ? hist[((31 - lane) << 6) | ls] : 0u;
+  const uint32_t inc2 = wave_scan_incl(c);
+  if (lane < 32 && (inc2 - c) < need2 && need2 <= inc2) {
+    ctl[0] = ls * 32 + 31 - lane; ctl[1] = (int)(need2 - (inc2 - c)); ctl[2] = (int)c;
+  }
+}
+
+#ifdef SPARQ_TIMELINE
+#define TL_MARK(slot) do { if (tid == 0 && a.idx_out) a.idx_out[(size_t)blockIdx.x * a.idx_stride + (slot)] = (int)wall_clock64(); } while (0)
+#else
+#define TL_MARK(slot) do {} while (0)
+#endif
+
 template <class T, int DH>
-__global__ __launch_bounds__(NT) void sparq_decode_fused(const DecodeArgs a) {
+__global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) {
   extern __shared__ __align__(16) uint32_t smem[];
   const Lds L = carve<DH>(smem, a.S_max);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  TL_MARK(0);
+#ifdef SPARQ_TIMELINE
+  if (tid == 0 && a.idx_out) {
+    a.idx_out[(size_t)blockIdx.x * a.idx_stride + 8] = __builtin_amdgcn_s_getreg(63492);   // HW_ID
+    a.idx_out[(size_t)blockIdx.x * a.idx_stride + 9] = __builtin_amdgcn_s_getreg(63508);   // XCC_ID
+  }
+#endif
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of units so
   // that the query heads of one KV group share an L2.
@@ -82,6 +121,8 @@ __global__ __launch_bounds__(NT) void sparq_decode_fused(const DecodeArgs a) {
   const int hk = h / (a.H / a.H_kv);
   const size_t kv_head = (size_t)b * a.H_kv + hk;
 
+  uint16_t qcode = 0;
+  if (tid < DH) qcode = reinterpret_cast<const uint16_t*>(a.q)[(size_t)u * DH + tid];
   int S = a.seq_lens[b];
   if (S < 0 || S > a.S_max) {
     if (tid == 0) atomicOr(a.err, 8);
@@ -101,21 +142,38 @@ __global__ __launch_bounds__(NT) void sparq_decode_fused(const DecodeArgs a) {
   }
 
   // ---------------- stage 0: top-r components of |q|, temperature ----------------
+  for (int i = tid; i < 2 * kRadixBins; i += NT) L.hist[i] = 0u;
   if (tid < DH) {
-    uint16_t c = reinterpret_cast<const uint16_t*>(a.q)[(size_t)u * DH + tid];
-    L.mag[tid] = c & 0x7fffu;
-    L.qf[tid] = T::widen(c);
+    L.mag[tid] = qcode & 0x7fffu;
+    L.qf[tid] = T::widen(qcode);
+  }
+  __syncthreads();
+  {
+    // rank of channel j = number of channels that precede it in (magnitude descending, index
+    // ascending) order; the NT threads split the DH x DH comparisons
+    constexpr int SL = NT / DH, PER = DH / SL;
+    const int j = tid % DH, slice = tid / DH;
+    const uint32_t mine = L.mag[j];
+    int partial = 0;
+#pragma unroll
+    for (int i4 = 0; i4 < PER; i4 += 4) {
+      const int i = slice * PER + i4;
+      const uint4 m = *reinterpret_cast<const uint4*>(L.mag + i);
+      partial += (m.x > mine) || (m.x == mine && i < j);
+      partial += (m.y > mine) || (m.y == mine && i + 1 < j);
+      partial += (m.z > mine) || (m.z == mine && i + 2 < j);
+      partial += (m.w > mine) || (m.w == mine && i + 3 < j);
+    }
+    reinterpret_cast<int*>(L.part)[slice * DH + j] = partial;
   }
   __syncthreads();
   bool sel = false;
   float aq = 0.0f;
   if (tid < DH) {
-    const uint32_t mine = L.mag[tid];
+    constexpr int SL = NT / DH;
     int rank = 0;
-    for (int i = 0; i < DH; ++i) {
-      const uint32_t m = L.mag[i];
-      rank += (m > mine) || (m == mine && i < tid);
-    }
+#pragma unroll
+    for (int s = 0; s < SL; ++s) rank += reinterpret_cast<const int*>(L.part)[s * DH + tid];
     sel = rank < a.r;
     aq = fabsf(L.qf[tid]);
   }
@@ -128,7 +186,14 @@ __global__ __launch_bounds__(NT) void sparq_decode_fused(const DecodeArgs a) {
     __syncthreads();
     int off = 0;
     for (int w = 0; w < wave; ++w) off += (int)L.wcnt[w];
-    if (sel) { L.chan[off + within] = tid; L.qs[off + within] = L.qf[tid]; }
+    if (sel) {
+      const int p = off + within;
+      L.chan[p] = tid; L.qs[p] = L.qf[tid];
+      // pad the list to a multiple of 8 with the last channel at weight 0: stage 1 then works on
+      // whole batches of 8 rows with no per-row predicate (the extra loads repeat a line just read)
+      if (p == a.r - 1)
+        for (int pp = a.r; pp < ((a.r + 7) & ~7); ++pp) { L.chan[pp] = tid; L.qs[pp] = 0.0f; }
+    }
   }
   float l1_all = 0.0f, l1_sel = 0.0f;
 #pragma unroll
@@ -136,39 +201,72 @@ __global__ __launch_bounds__(NT) void sparq_decode_fused(const DecodeArgs a) {
   const float tau = l1_all > 0.0f ? sqrtf((float)DH * l1_sel / l1_all) : sqrtf((float)DH);
   __syncthreads();
   if (a.chan_out && tid < a.r) a.chan_out[(size_t)u * a.r + tid] = L.chan[tid];
+  TL_MARK(1);
 
+#ifdef SPARQ_STAGGER_TICKS
+  if (blockIdx.x >= (unsigned)(U / 2)) {
+    const uint64_t t_begin = wall_clock64();
+    while (wall_clock64() - t_begin < (uint64_t)SPARQ_STAGGER_TICKS) __builtin_amdgcn_s_sleep(16);
+  }
+#endif
   // ---------------- stage 1: approximate logits over the r selected channel rows ----------------
+  // A thread owns chunks of 8 consecutive positions (16 bytes of every channel row); the loads of
+  // the next 8 channels are in flight while the current 8 are accumulated.  Each finished key is
+  // also counted into the first digit histogram, so the first select pass costs no extra sweep.
   const int r = a.r;
   const size_t row_bytes = (size_t)a.S_max * 2;
   const char* Kt_head = reinterpret_cast<const char*>(a.Kt) + kv_head * DH * row_bytes;
-  const int n_chunks = (S + 7) >> 3;   // 8 positions (16 bytes) per thread per channel row
+  const int n_chunks = (S + 7) >> 3;
   float tmax = -INFINITY;
+  const int n_batches = (r + 7) >> 3;   // batches of 8 channel rows (list padded in stage 0)
+  auto issue = [&](uint4 (&v)[8], uint32_t voff, int batch) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const int ch = __builtin_amdgcn_readfirstlane(L.chan[batch * 8 + t]);   // uniform: scalar row base
+      v[t] = load16(Kt_head + (size_t)ch * row_bytes + voff);
+    }
+  };
+  auto consume = [&](const uint4 (&v)[8], float (&acc)[8], int batch) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const float qv = L.qs[batch * 8 + t];
+      float f[8];
+      unpack8<T>(v[t], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = fmaf(f[e], qv, acc[e]);
+    }
+  };
   for (int c = tid; c < n_chunks; c += NT) {
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const char* base = Kt_head + (size_t)c * 16;
-    for (int j0 = 0; j0 < r; j0 += 8) {
-      uint4 v[8];
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const int j = (j0 + t < r) ? j0 + t : r - 1;
-        v[t] = load16(base + (size_t)L.chan[j] * row_bytes);
-      }
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        if (j0 + t < r) {
-          const float qv = L.qs[j0 + t];
-          float f[8];
-          unpack8<T>(v[t], f);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[e] = fmaf(f[e], qv, acc[e]);
-        }
-      }
+    const uint32_t voff = (uint32_t)c * 16u;
+    uint4 va[8], vb[8];
+    // software pipeline over the batches: one batch of 8 loads is always in flight behind the
+    // one being accumulated
+    issue(va, voff, 0);
+    int bi = 0;
+    for (; bi + 2 < n_batches; bi += 2) {
+      issue(vb, voff, bi + 1);
+      consume(va, acc, bi);
+      issue(va, voff, bi + 2);
+      consume(vb, acc, bi + 1);
+    }
+    if (bi + 1 < n_batches) {
+      issue(vb, voff, bi + 1);
+      consume(va, acc, bi);
+      consume(vb, acc, bi + 1);
+    } else {
+      consume(va, acc, bi);
     }
     uint32_t kx[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      if (c * 8 + e < S) { tmax = fmaxf(tmax, acc[e]); kx[e] = float_to_key(acc[e]); }
-      else kx[e] = 0u;
+      if (c * 8 + e < S) {
+        tmax = fmaxf(tmax, acc[e]);
+        kx[e] = float_to_key(acc[e]);
+        atomicAdd(&L.hist[hist_slot(kx[e] >> 21)], 1u);
+      } else {
+        kx[e] = 0u;
+      }
     }
     uint4* dst = reinterpret_cast<uint4*>(L.keys + c * 8);
     dst[0] = make_uint4(kx[0], kx[1], kx[2], kx[3]);
@@ -181,45 +279,48 @@ __global__ __launch_bounds__(NT) void sparq_decode_fused(const DecodeArgs a) {
 #pragma unroll
   for (int w = 1; w < NW; ++w) dmax = fmaxf(dmax, L.red[w]);
 
+  TL_MARK(2);
+#if defined(SPARQ_STOP_AFTER) && SPARQ_STOP_AFTER == 1
+  if (tid < DH) out[tid] = (uint16_t)(L.keys[tid] + __float_as_uint(dmax));
+  return;
+#endif
   // ---------------- stage 2a: radix select of the kq-th largest key ----------------
+  // Digits of 11, 11 and 10 bits from the top.  Pass p counts into hist[p & 1]; the other buffer
+  // is cleared meanwhile.  One wave finds the threshold bin, everyone picks it up after a barrier.
   uint32_t pmask = 0u, pval = 0u;   // decided high bits of the threshold key
   int need = kq;                    // how many keys equal to the threshold on the decided bits are taken
   for (int pass = 0; pass < 3; ++pass) {
     const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
     const uint32_t dmask = pass == 2 ? 0x3ffu : 0x7ffu;
-    for (int i = tid; i < kRadixBins; i += NT) L.hist[i] = 0u;
-    __syncthreads();
-    for (int i = tid; i < S; i += NT) {
-      const uint32_t key = L.keys[i];
-      if ((key & pmask) == pval) atomicAdd(&L.hist[(key >> shift) & dmask], 1u);
-    }
-    __syncthreads();
-    // thread t owns bins 4t..4t+3; find the bin where the count from the top reaches `need`
-    const uint4 own = reinterpret_cast<const uint4*>(L.hist)[tid];
-    const uint32_t mine = own.x + own.y + own.z + own.w;
-    uint32_t total;
-    const uint32_t below = block_scan_excl(mine, L.wcnt, lane, wave, &total);
-    const uint32_t above = total - below - mine;   // keys in bins beyond this thread's
-    if (above < (uint32_t)need && (uint32_t)need <= above + mine) {
-      const uint32_t cnt[4] = {own.x, own.y, own.z, own.w};
-      uint32_t run = above;
-      for (int d = 3; d >= 0; --d) {
-        if (run + cnt[d] >= (uint32_t)need) {
-          L.ctl[0] = tid * 4 + d; L.ctl[1] = need - (int)run; L.ctl[2] = (int)cnt[d];
-          break;
-        }
-        run += cnt[d];
+    uint32_t* hist = L.hist + (pass & 1) * kRadixBins;
+    if (pass > 0) {
+      uint32_t* other = L.hist + ((pass + 1) & 1) * kRadixBins;   // free since the last barrier
+      for (int i = tid; i < kRadixBins; i += NT) other[i] = 0u;
+      for (int c = tid; c < n_chunks; c += NT) {
+        const uint4* src = reinterpret_cast<const uint4*>(L.keys + c * 8);
+        const uint4 lo = src[0], hi = src[1];
+        const uint32_t kx[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (c * 8 + e < S && (kx[e] & pmask) == pval) atomicAdd(&hist[hist_slot((kx[e] >> shift) & dmask)], 1u);
       }
+      if (pass == 1) TL_MARK(7);
+      __syncthreads();
     }
+    if (pass == 1) TL_MARK(14);
+    if (wave == 0) find_threshold_bin(hist, need, lane, L.ctl);
+    if (pass == 0) TL_MARK(13);
+    if (pass == 1) TL_MARK(15);
     __syncthreads();
     pval |= (uint32_t)L.ctl[0] << shift;
     pmask |= dmask << shift;
     need = L.ctl[1];
     const int in_bin = L.ctl[2];
-    __syncthreads();
+    TL_MARK(10 + pass);
     if (need == in_bin) break;   // every key matching the decided bits is taken: no ties to split
   }
 
+  TL_MARK(3);
   // ---------------- stage 2b: ordered compaction, alpha ----------------
   // Taken: keys above the threshold on the decided bits, plus the first `need` (by position)
   // keys equal to it.  The position list overwrites the key array from the front; a thread
@@ -227,8 +328,13 @@ __global__ __launch_bounds__(NT) void sparq_decode_fused(const DecodeArgs a) {
   const float esc = kLog2e / tau;
   float zsum = 0.0f, asum = 0.0f;
   uint32_t run_gt = 0, run_eq = 0;
+#ifdef SPARQ_TIMELINE
+  int32_t* idx_out = nullptr;
+#else
   int32_t* idx_out = a.idx_out ? a.idx_out + (size_t)u * a.idx_stride : nullptr;
-  for (int c0 = 0; c0 < n_chunks; c0 += NT) {
+#endif
+  int sweep = 0;
+  for (int c0 = 0; c0 < n_chunks; c0 += NT, ++sweep) {
     const int c = c0 + tid;
     uint32_t kx[8];
     if (c < n_chunks) {
@@ -251,7 +357,7 @@ __global__ __launch_bounds__(NT) void sparq_decode_fused(const DecodeArgs a) {
       n_gt += g; n_eq += q;
     }
     uint32_t total;
-    const uint32_t ex = block_scan_excl(n_gt | (n_eq << 16), L.wcnt, lane, wave, &total);
+    const uint32_t ex = block_scan_excl(n_gt | (n_eq << 16), L.wcnt + (sweep & 1) * NW, lane, wave, &total);
     const uint32_t gt_before = run_gt + (ex & 0xffffu);
     uint32_t eq_before = run_eq + (ex >> 16);
     uint32_t o = gt_before + (eq_before < (uint32_t)need ? eq_before : (uint32_t)need);
@@ -287,6 +393,11 @@ __global__ __launch_bounds__(NT) void sparq_decode_fused(const DecodeArgs a) {
   }
   if (idx_out) for (int n = kq + tid; n < a.idx_stride; n += NT) idx_out[n] = -1;
 
+  TL_MARK(4);
+#if defined(SPARQ_STOP_AFTER) && SPARQ_STOP_AFTER == 2
+  if (tid < DH) out[tid] = (uint16_t)(L.keys[tid] + __float_as_uint(alpha));
+  return;
+#endif
   // ---------------- stage 3: exact attention over the gathered rows, blend ----------------
   constexpr int LPR = DH / 8;          // lanes per row (16 bytes each)
   constexpr int RPW = kWave / LPR;     // rows per wave per load
@@ -302,17 +413,18 @@ __global__ __launch_bounds__(NT) void sparq_decode_fused(const DecodeArgs a) {
   for (int e = 0; e < 8; ++e) q8[e] = L.qf[sub * 8 + e] * qscale;
   float m_run = -INFINITY, l_run = 0.0f;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  for (int n0 = 0; n0 < kq; n0 += RPI * UNR) {
-    uint4 kr[UNR], vr[UNR];
-    bool ok[UNR];
+  constexpr int GROUP = RPI * UNR;          // rows the workgroup covers per group of loads
+  const int n_groups = (kq + GROUP - 1) / GROUP;
+  auto issue3 = [&](uint4 (&kr)[UNR], uint4 (&vr)[UNR], int g) {
 #pragma unroll
     for (int t = 0; t < UNR; ++t) {
-      const int n = n0 + t * RPI + slot;
-      ok[t] = n < kq;
-      const size_t off = (size_t)pos[ok[t] ? n : 0] * (size_t)(DH * 2);
+      const int n = g * GROUP + t * RPI + slot;
+      const uint32_t off = (uint32_t)pos[n < kq ? n : kq - 1] * (uint32_t)(DH * 2);   // < S_max * 512 bytes
       kr[t] = load16(K_head + off);
       vr[t] = load16(V_head + off);
     }
+  };
+  auto consume3 = [&](const uint4 (&kr)[UNR], const uint4 (&vr)[UNR], int g) {
 #pragma unroll
     for (int t = 0; t < UNR; ++t) {
       float f[8];
@@ -322,7 +434,7 @@ __global__ __launch_bounds__(NT) void sparq_decode_fused(const DecodeArgs a) {
       for (int e = 0; e < 8; ++e) dot = fmaf(f[e], q8[e], dot);
 #pragma unroll
       for (int o = 1; o < LPR; o <<= 1) dot += __shfl_xor(dot, o);
-      if (ok[t]) {
+      if (g * GROUP + t * RPI + slot < kq) {
         const float m_new = fmaxf(m_run, dot);
         const float sc = exp2f(m_run - m_new), pr = exp2f(dot - m_new);
         unpack8<T>(vr[t], f);
@@ -331,6 +443,24 @@ __global__ __launch_bounds__(NT) void sparq_decode_fused(const DecodeArgs a) {
         for (int e = 0; e < 8; ++e) acc[e] = acc[e] * sc + pr * f[e];
         m_run = m_new;
       }
+    }
+  };
+  {
+    uint4 ka[UNR], va3[UNR], kb3[UNR], vb3[UNR];
+    issue3(ka, va3, 0);
+    int g = 0;
+    for (; g + 2 < n_groups; g += 2) {
+      issue3(kb3, vb3, g + 1);
+      consume3(ka, va3, g);
+      issue3(ka, va3, g + 2);
+      consume3(kb3, vb3, g + 1);
+    }
+    if (g + 1 < n_groups) {
+      issue3(kb3, vb3, g + 1);
+      consume3(ka, va3, g);
+      consume3(kb3, vb3, g + 1);
+    } else {
+      consume3(ka, va3, g);
     }
   }
   // merge the row groups of a wave, then the waves
@@ -367,6 +497,7 @@ __global__ __launch_bounds__(NT) void sparq_decode_fused(const DecodeArgs a) {
     if (!(a.flags & 1u)) y = alpha * y3 + (1.0f - alpha) * a.v_mean[kv_head * DH + tid];
     out[tid] = T::narrow(y);
   }
+  TL_MARK(5);
 }
 
 template <class T, int DH>
@@ -385,7 +516,7 @@ hipError_t launch_one(const DecodeArgs& a, hipStream_t s) {
 }  // namespace
 
 size_t decode_lds_bytes(int S_max, int d_h) {
-  return 4 * ((size_t)S_max + kRadixBins + (size_t)NW * (d_h + 2) + 4 * (size_t)d_h + 32 + 16 + 8);
+  return 4 * ((size_t)S_max + 2 * kRadixBins + (size_t)NW * (d_h + 2) + 4 * (size_t)d_h + 32 + 16 + 8);
 }
 
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s) {
