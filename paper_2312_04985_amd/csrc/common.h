@@ -50,15 +50,48 @@ __device__ __forceinline__ float key_to_float(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
-// ---- wave64 primitives ----
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+// ---- wave64 primitives (DPP: no LDS traffic, a few cycles each) ----
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float lane_f(float v, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+// Butterfly all-reduce over aligned groups of N lanes (N = 8 or 16): xor 1 and xor 2 by quad
+// permutes, then half-row mirror and row mirror, which act as xor 4 / xor 8 once the quads (halves)
+// are uniform.  Every step adds a pair commutatively, so all lanes of a group end with the same bits.
+template <int N>
+__device__ __forceinline__ float group_sum(float v) {
+  v += dpp_f<0xB1>(v);                  // quad_perm [1,0,3,2]
+  v += dpp_f<0x4E>(v);                  // quad_perm [2,3,0,1]
+  v += dpp_f<0x141>(v);                 // row_half_mirror
+  if (N >= 16) v += dpp_f<0x140>(v);    // row_mirror
   return v;
 }
+template <int N>
+__device__ __forceinline__ float group_max(float v) {
+  v = fmaxf(v, dpp_f<0xB1>(v));
+  v = fmaxf(v, dpp_f<0x4E>(v));
+  v = fmaxf(v, dpp_f<0x141>(v));
+  if (N >= 16) v = fmaxf(v, dpp_f<0x140>(v));
+  return v;
+}
+// reductions over the whole wave: the result is wave-uniform
+__device__ __forceinline__ float wave_sum(float v) {
+  v = group_sum<16>(v);
+  return (lane_f(v, 0) + lane_f(v, 16)) + (lane_f(v, 32) + lane_f(v, 48));
+}
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  v = group_max<16>(v);
+  return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
+}
+// sum over aligned groups of LPR lanes (8, 16 or 32), same value in every lane of a group
+template <int LPR>
+__device__ __forceinline__ float lanes_sum(float v) {
+  if (LPR == 8) return group_sum<8>(v);
+  v = group_sum<16>(v);
+  if (LPR == 32) v += __shfl_xor(v, 16);
   return v;
 }
 // inclusive prefix sum across the 64 lanes with DPP row shifts and row broadcasts

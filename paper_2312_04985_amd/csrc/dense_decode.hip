@@ -65,8 +65,7 @@ __global__ __launch_bounds__(DT) void dense_partial(const DenseArgs a) {
         float dot = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) dot = fmaf(kf[e], q8[t][e], dot);
-#pragma unroll
-        for (int o = 1; o < LPR; o <<= 1) dot += __shfl_xor(dot, o);
+        dot = lanes_sum<LPR>(dot);
         if (ok[u]) {
           const float m_new = fmaxf(m_run[t], dot);
           const float sc = exp2f(m_run[t] - m_new), pr = exp2f(dot - m_new);

@@ -94,7 +94,10 @@ __device__ __forceinline__ void find_threshold_bin(const uint32_t* hist, int nee
 }
 
 #ifdef SPARQ_TIMELINE
-#define TL_MARK(slot) do { if (tid == 0 && a.idx_out) a.idx_out[(size_t)blockIdx.x * a.idx_stride + (slot)] = (int)wall_clock64(); } while (0)
+#ifndef SPARQ_TL_MASK
+#define SPARQ_TL_MASK 0xffffffffu
+#endif
+#define TL_MARK(slot) do { if (((SPARQ_TL_MASK >> (slot)) & 1u) && tid == 0 && a.idx_out) a.idx_out[(size_t)blockIdx.x * a.idx_stride + (slot)] = (int)wall_clock64(); } while (0)
 #else
 #define TL_MARK(slot) do {} while (0)
 #endif
@@ -124,6 +127,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   uint16_t qcode = 0;
   if (tid < DH) qcode = reinterpret_cast<const uint16_t*>(a.q)[(size_t)u * DH + tid];
   int S = a.seq_lens[b];
+  TL_MARK(15);
   if (S < 0 || S > a.S_max) {
     if (tid == 0) atomicOr(a.err, 8);
     S = S < 0 ? 0 : a.S_max;
@@ -142,73 +146,66 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   }
 
   // ---------------- stage 0: top-r components of |q|, temperature ----------------
+  // Channel j gets the sort key (|q_j| as its 15-bit code) << 9 | (511 - j): keys are distinct and
+  // "larger key" is exactly "larger magnitude, or equal magnitude and lower channel".
   for (int i = tid; i < 2 * kRadixBins; i += NT) L.hist[i] = 0u;
   if (tid < DH) {
-    L.mag[tid] = qcode & 0x7fffu;
+    L.mag[tid] = ((uint32_t)(qcode & 0x7fffu) << 9) | (uint32_t)(511 - tid);
     L.qf[tid] = T::widen(qcode);
   }
   __syncthreads();
+  TL_MARK(13);
+  int* rankp = reinterpret_cast<int*>(L.part);   // [NT / DH][DH] partial ranks
   {
-    // rank of channel j = number of channels that precede it in (magnitude descending, index
-    // ascending) order; the NT threads split the DH x DH comparisons
+    // rank of channel j = number of larger keys; the NT threads split the DH x DH comparisons
     constexpr int SL = NT / DH, PER = DH / SL;
     const int j = tid % DH, slice = tid / DH;
     const uint32_t mine = L.mag[j];
     int partial = 0;
 #pragma unroll
     for (int i4 = 0; i4 < PER; i4 += 4) {
-      const int i = slice * PER + i4;
-      const uint4 m = *reinterpret_cast<const uint4*>(L.mag + i);
-      partial += (m.x > mine) || (m.x == mine && i < j);
-      partial += (m.y > mine) || (m.y == mine && i + 1 < j);
-      partial += (m.z > mine) || (m.z == mine && i + 2 < j);
-      partial += (m.w > mine) || (m.w == mine && i + 3 < j);
+      const uint4 m = *reinterpret_cast<const uint4*>(L.mag + slice * PER + i4);
+      partial += (m.x > mine) + (m.y > mine) + (m.z > mine) + (m.w > mine);
     }
-    reinterpret_cast<int*>(L.part)[slice * DH + j] = partial;
+    rankp[slice * DH + j] = partial;
   }
   __syncthreads();
-  bool sel = false;
-  float aq = 0.0f;
-  if (tid < DH) {
-    constexpr int SL = NT / DH;
-    int rank = 0;
-#pragma unroll
-    for (int s = 0; s < SL; ++s) rank += reinterpret_cast<const int*>(L.part)[s * DH + tid];
-    sel = rank < a.r;
-    aq = fabsf(L.qf[tid]);
-  }
+  TL_MARK(14);
+  float tau;
   {
-    const uint64_t bal = __ballot(sel);
-    const int within = __popcll(bal & ((1ull << lane) - 1ull));
-    if (lane == 0) L.wcnt[wave] = (uint32_t)__popcll(bal);
-    const float l1a = wave_sum(aq), l1s = wave_sum(sel ? aq : 0.0f);
-    if (lane == 0) { L.red[wave] = l1a; L.red[NW + wave] = l1s; }
-    __syncthreads();
-    int off = 0;
-    for (int w = 0; w < wave; ++w) off += (int)L.wcnt[w];
-    if (sel) {
-      const int p = off + within;
-      L.chan[p] = tid; L.qs[p] = L.qf[tid];
-      // pad the list to a multiple of 8 with the last channel at weight 0: stage 1 then works on
-      // whole batches of 8 rows with no per-row predicate (the extra loads repeat a line just read)
-      if (p == a.r - 1)
-        for (int pp = a.r; pp < ((a.r + 7) & ~7); ++pp) { L.chan[pp] = tid; L.qs[pp] = 0.0f; }
-    }
-  }
-  float l1_all = 0.0f, l1_sel = 0.0f;
+    // Every wave finishes the selection for all channels by itself (no further exchange): ranks,
+    // ballots and the L1 sums are recomputed per wave; wave g writes the list entries of channels
+    // 64g..64g+63.  The list is padded to a multiple of 8 with the last channel at weight 0, so
+    // stage 1 works on whole batches of 8 rows (the extra loads repeat a line just read).
+    constexpr int SL = NT / DH, NG = DH / kWave;
+    const int r8 = (a.r + 7) & ~7;
+    int before = 0;
+    float l1a = 0.0f, l1s = 0.0f;
 #pragma unroll
-  for (int w = 0; w < NW; ++w) { l1_all += L.red[w]; l1_sel += L.red[NW + w]; }
-  const float tau = l1_all > 0.0f ? sqrtf((float)DH * l1_sel / l1_all) : sqrtf((float)DH);
+    for (int g = 0; g < NG; ++g) {
+      const int jj = g * kWave + lane;
+      int rank = 0;
+#pragma unroll
+      for (int s = 0; s < SL; ++s) rank += rankp[s * DH + jj];
+      const bool sel = rank < a.r;
+      const float qv = L.qf[jj], aq = fabsf(qv);
+      const uint64_t bal = __ballot(sel);
+      if (g == wave && sel) {
+        const int p = before + __popcll(bal & ((1ull << lane) - 1ull));
+        L.chan[p] = jj; L.qs[p] = qv;
+        if (p == a.r - 1)
+          for (int pp = a.r; pp < r8; ++pp) { L.chan[pp] = jj; L.qs[pp] = 0.0f; }
+      }
+      before += __popcll(bal);
+      l1a += aq; l1s += sel ? aq : 0.0f;
+    }
+    const float l1_all = wave_sum(l1a), l1_sel = wave_sum(l1s);
+    tau = l1_all > 0.0f ? sqrtf((float)DH * l1_sel / l1_all) : sqrtf((float)DH);
+  }
   __syncthreads();
   if (a.chan_out && tid < a.r) a.chan_out[(size_t)u * a.r + tid] = L.chan[tid];
   TL_MARK(1);
 
-#ifdef SPARQ_STAGGER_TICKS
-  if (blockIdx.x >= (unsigned)(U / 2)) {
-    const uint64_t t_begin = wall_clock64();
-    while (wall_clock64() - t_begin < (uint64_t)SPARQ_STAGGER_TICKS) __builtin_amdgcn_s_sleep(16);
-  }
-#endif
   // ---------------- stage 1: approximate logits over the r selected channel rows ----------------
   // A thread owns chunks of 8 consecutive positions (16 bytes of every channel row); the loads of
   // the next 8 channels are in flight while the current 8 are accumulated.  Each finished key is
@@ -304,13 +301,9 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
         for (int e = 0; e < 8; ++e)
           if (c * 8 + e < S && (kx[e] & pmask) == pval) atomicAdd(&hist[hist_slot((kx[e] >> shift) & dmask)], 1u);
       }
-      if (pass == 1) TL_MARK(7);
       __syncthreads();
     }
-    if (pass == 1) TL_MARK(14);
     if (wave == 0) find_threshold_bin(hist, need, lane, L.ctl);
-    if (pass == 0) TL_MARK(13);
-    if (pass == 1) TL_MARK(15);
     __syncthreads();
     pval |= (uint32_t)L.ctl[0] << shift;
     pmask |= dmask << shift;
@@ -432,8 +425,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
       float dot = 0.0f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) dot = fmaf(f[e], q8[e], dot);
-#pragma unroll
-      for (int o = 1; o < LPR; o <<= 1) dot += __shfl_xor(dot, o);
+      dot = lanes_sum<LPR>(dot);
       if (g * GROUP + t * RPI + slot < kq) {
         const float m_new = fmaxf(m_run, dot);
         const float sc = exp2f(m_run - m_new), pr = exp2f(dot - m_new);
