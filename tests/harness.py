@@ -180,3 +180,72 @@ def compare_decode(b: Built, q: torch.Tensor, *, flags: int = 0, check_state: bo
     stats.update(alpha_err=float(a_err), out_err=float(err.max()), dense_err=float(derr.max()),
                  alpha_min=float(ref_g.alpha.min()), alpha_max=float(ref_g.alpha.max()))
     return stats
+
+
+def compare_sampled(b: Built, q: torch.Tensor, *, n_units: int = 48, flags: int = 0, seed: int = 0,
+                    with_dense: bool = True) -> dict:
+    """Full-size run on the GPU, oracle on a seeded sample of (sequence, KV head) units: only the
+    sampled heads' rows travel to the host.  The sample is handed to the oracle as a batch of
+    n_units sequences with one KV head and g query heads each; checks are those of compare_decode,
+    including the cache state of the sampled heads."""
+    w, c = b.w, b.cache
+    g = w.H // w.H_kv
+    dev_k = None if b.k_per_seq is None else b.k_per_seq.to(c.device)
+    kq_all = torch.minimum(b.k_per_seq if b.k_per_seq is not None else torch.full_like(b.seq_lens, w.k), b.seq_lens)
+    c.with_params(w.r, w.k, flags)
+    out, alpha, idx, chan = c.decode(q, dev_k, aux=True, idx_stride=max(int(kq_all.max()), 1))
+    dense = c.dense(q) if with_dense else None
+    torch.cuda.synchronize()
+    assert c.error_flags() == 0
+
+    rng = np.random.default_rng(seed)
+    total = w.B * w.H_kv
+    picks = np.sort(rng.choice(total, size=min(n_units, total), replace=False))
+    n = len(picks)
+    S_max = c.S_max
+    Kh = np.zeros((n, 1, S_max, w.d_h), dtype=np.uint16); Vh = np.zeros_like(Kh)
+    qh = np.zeros((n, g, w.d_h), dtype=np.uint16)
+    seq = np.zeros(n, dtype=np.int32); kps = None if b.k_per_seq is None else np.zeros(n, dtype=np.int32)
+    sub = lambda t, bi, hk: t[bi, hk * g:(hk + 1) * g].cpu().numpy()
+    g_out = np.zeros((n, g, w.d_h)); g_alpha = np.zeros((n, g)); g_dense = np.zeros((n, g, w.d_h))
+    g_idx = np.zeros((n, g, idx.shape[-1]), dtype=np.int32); g_chan = np.zeros((n, g, w.r), dtype=np.int32)
+    for i, p in enumerate(picks):
+        bi, hk = divmod(int(p), w.H_kv)
+        s = int(b.seq_lens[bi]); seq[i] = s
+        if kps is not None:
+            kps[i] = int(b.k_per_seq[bi])
+        Kh[i, 0, :s] = W.to_codes(b.K_src[bi, hk, :s]); Vh[i, 0, :s] = W.to_codes(b.V_src[bi, hk, :s])
+        qh[i] = W.to_codes(q[bi, hk * g:(hk + 1) * g])
+        # cache state of this head: both key layouts bit-exact
+        assert np.array_equal(W.to_codes(c.K[bi, hk, :s]), Kh[i, 0, :s]), "K rows"
+        assert np.array_equal(W.to_codes(c.V[bi, hk, :s]), Vh[i, 0, :s]), "V rows"
+        assert np.array_equal(W.to_codes(c.Kt[bi, hk, :, :s]), Kh[i, 0, :s].T), "Kt columns"
+        g_out[i] = sub(out.float(), bi, hk); g_alpha[i] = sub(alpha, bi, hk)
+        g_idx[i] = sub(idx, bi, hk); g_chan[i] = sub(chan, bi, hk)
+        if with_dense:
+            g_dense[i] = sub(dense.float(), bi, hk)
+    vbar = O.mean_value(Vh, seq, dtype=w.dtype_code)[:, 0]
+    got_vm = np.stack([c.v_mean[divmod(int(p), w.H_kv)].cpu().numpy() for p in picks]).astype(np.float64)
+    assert np.abs(got_vm - vbar).max() <= VMEAN_TOL, "v_mean"
+
+    ref = O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags, k_per_seq=kps, want_z=True)
+    Kf = O.to_double(Kh, w.dtype_code); qf = O.to_double(qh, w.dtype_code)
+    assert np.array_equal(g_chan, ref.i1), "i1 (top-r channels) must match exactly"
+    stride = ref.i2.shape[-1]
+    assert (g_idx[:, :, stride:] == -1).all()
+    ws = W.scaled(w, B=n, H=g, H_kv=1)
+    stats = check_positions(g_idx[:, :, :stride], ref, Kf, qf, seq, kps, ws)
+    ref_g = ref if stats["exact_sets"] == stats["units"] else \
+        O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags, k_per_seq=kps,
+                       given_i2=np.ascontiguousarray(g_idx[:, :, :stride]))
+    a_err = np.abs(g_alpha - ref_g.alpha).max()
+    assert a_err <= ALPHA_TOL, f"alpha error {a_err}"
+    err = np.abs(g_out - ref_g.y)
+    assert (err <= out_tolerance(w.dtype_code, ref_g.y)).all(), f"output error {err.max()}"
+    stats.update(sampled_kv_heads=n, alpha_err=float(a_err), out_err=float(err.max()))
+    if with_dense:
+        yd = O.dense_decode(Kh, Vh, qh, seq, dtype=w.dtype_code)
+        derr = np.abs(g_dense - yd)
+        assert (derr <= out_tolerance(w.dtype_code, yd)).all(), f"dense output error {derr.max()}"
+        stats.update(dense_err=float(derr.max()))
+    return stats

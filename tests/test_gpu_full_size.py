@@ -1,0 +1,33 @@
+"""GPU parity at the full sizes of the five named workloads, in the launch configuration the
+benchmark uses.  The whole batch runs on the GPU; the oracle checks a seeded sample of
+(sequence, KV head) units (all query heads of each), whose rows alone are copied to the host."""
+import sys
+
+import pytest
+import torch
+
+from paper_2312_04985_amd import workloads as W
+
+import harness as Hn
+
+pytestmark = pytest.mark.gpu
+C = W.CONFIGS
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.mark.parametrize("name,n_units,singles", [
+    ("c1_single_head", 1, 2), ("c2_llama2_7b", 48, 2), ("c3_llama3_8b_gqa", 8, 1),
+    ("c4_large_batch", 40, 1), ("c5_gemma_7b_ragged", 24, 1), ("paper_table2", 32, 1)])
+def test_full_size_sampled(name, n_units, singles):
+    w = C[name]
+    say(f"[full-size] {name}: B={w.B} H={w.H}/{w.H_kv} d_h={w.d_h} S={w.S} r={w.r} k={w.k} {w.dtype} ragged={w.ragged}")
+    b = Hn.build_cache(w, single_appends=singles, poison=None)
+    say("   cache built:", tuple(b.cache.K.shape), "seq_lens", b.seq_lens[:8].tolist())
+    q = W.draw_queries(w, b.K_src, b.seq_lens, n=1)[0]
+    stats = Hn.compare_sampled(b, q, n_units=n_units, seed=w.seed)
+    say("   ", stats)
+    del b
+    torch.cuda.empty_cache()
