@@ -103,91 +103,107 @@ def main():
     def ptr(t):
         return None if t is None else vp(t.data_ptr())
 
+    # Every cache copy has two (v_mean, seq_lens) pairs: the one-launch step reads one pair and
+    # writes the other, and the roles swap on the next visit of that copy.
+    vm = [[c.v_mean, torch.empty_like(c.v_mean)] for c in caches]
+    sl = [[c.seq_lens, torch.empty_like(c.seq_lens)] for c in caches]
+    cs = [[B.make_cache(c.K, c.Kt, c.V, vm[i][p], sl[i][p]) for p in (0, 1)] for i, c in enumerate(caches)]
+    par = [0] * copies
+
     # pre-marshalled argument tuples: the timed loops only call into the C ABI
-    app_args, dec_args, den_args = [], [], []
-    for i in range(copies * n_pool):
-        c, j = caches[i % copies], i % n_pool
-        ws, wsb = ptr(c.workspace), c.workspace.numel()
-        app_args.append((ctypes.byref(c.shape), ctypes.byref(c.cache), ptr(kn_pool[j]), ptr(vn_pool[j]), 1, None, ws, wsb, stream))
-        dec_args.append((ctypes.byref(c.shape), ctypes.byref(c.cache), ptr(q_pool[j]), ptr(kps_dev), ptr(outs[i % 2]),
-                         None, None, 0, None, ws, wsb, stream))
-        den_args.append((ctypes.byref(c.shape), ctypes.byref(c.cache), ptr(q_pool[j]), ptr(outs[i % 2]), ws, wsb, stream))
-    n_args = len(app_args)
+    def args_for(ci, p, j, o):
+        c = caches[ci]
+        sh, cc, ws, wsb = ctypes.byref(c.shape), ctypes.byref(cs[ci][p]), ptr(c.workspace), c.workspace.numel()
+        return {
+            "step": (sh, cc, ptr(kn_pool[j]), ptr(vn_pool[j]), ptr(vm[ci][1 - p]), ptr(sl[ci][1 - p]), ptr(q_pool[j]),
+                     ptr(kps_dev), ptr(outs[o]), None, None, 0, None, ws, wsb, stream),
+            "append": (sh, cc, ptr(kn_pool[j]), ptr(vn_pool[j]), 1, None, ws, wsb, stream),
+            "decode": (sh, cc, ptr(q_pool[j]), ptr(kps_dev), ptr(outs[o]), None, None, 0, None, ws, wsb, stream),
+            "dense": (sh, cc, ptr(q_pool[j]), ptr(outs[o]), ws, wsb, stream),
+        }
+    table = [[[args_for(ci, p, j, (ci + j) % 2) for j in range(n_pool)] for p in (0, 1)] for ci in range(copies)]
 
     def restore():
-        for c, (vm, sl) in zip(caches, snap):
-            c.v_mean.copy_(vm); c.seq_lens.copy_(sl)
+        for ci, (v0, s0) in enumerate(snap):
+            vm[ci][0].copy_(v0); sl[ci][0].copy_(s0); par[ci] = 0
         torch.cuda.synchronize()
 
-    def step(i):
-        rc = lib.sparq_kv_append(*app_args[i % n_args]) or lib.sparq_decode(*dec_args[i % n_args])
+    def check(rc):
         if rc:
             raise RuntimeError(f"libsparq call failed: {B.status_string(rc)}")
 
+    def fused_step(i):            # the step: append + decode in one launch
+        ci = i % copies
+        check(lib.sparq_decode_step(*table[ci][par[ci]][i % n_pool]["step"]))
+        par[ci] ^= 1
+
+    def two_call_step(i):         # the same step as two launches (state updated in place)
+        a = table[i % copies][par[i % copies]][i % n_pool]
+        check(lib.sparq_kv_append(*a["append"]) or lib.sparq_decode(*a["decode"]))
+
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / n
+
+    def timed_events(fn, n):      # HIP events on the stream the kernels are launched on
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
     # ---- warm-up, then the timed region: exactly K steps between two device syncs ----
     for i in range(Wm):
-        step(i)
+        fused_step(i)
     restore()
-    t0 = time.perf_counter()
-    for i in range(K):
-        step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / K
-    flags = sum(c.error_flags() for c in caches)
+    ms_per_step = timed(fused_step, K)
+    flags = sum(B.sparq_async_error(c.workspace) for c in caches)
     if flags:
         raise RuntimeError(f"device error word set during the timed region: {flags}")
 
-    # ---- average launch duration of the dominant kernel (sparq_decode), HIP events on its stream ----
-    # K back-to-back launches over the same rotation between one pair of events: launch gaps included.
+    # ---- average launch duration of the dominant kernel (the one-launch step) over the same K steps,
+    # HIP events on its stream; K back-to-back launches, launch gaps included ----
     restore()
-    for i in range(copies):                  # every copy at the length its first timed decode saw
-        lib.sparq_kv_append(*app_args[i])
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(K):
-        lib.sparq_decode(*dec_args[i % n_args])
-    e1.record()
-    torch.cuda.synchronize()
-    dec_avg_ms = e0.elapsed_time(e1) / K
-    # and one launch at a time (adds the event/dispatch overhead of an isolated launch)
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
-    for i in range(K):
-        ev[i][0].record()
-        lib.sparq_decode(*dec_args[i % n_args])
-        ev[i][1].record()
-    torch.cuda.synchronize()
-    dec_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    step_avg_ms = timed_events(fused_step, K)
 
-    # appends alone (same rotation), for the record
+    # for the record: the step as two launches, the decode launch alone, the append launch alone
     restore()
-    torch.cuda.synchronize(); ta = time.perf_counter()
-    for i in range(K):
-        lib.sparq_kv_append(*app_args[i % n_args])
-    torch.cuda.synchronize(); append_ms = (time.perf_counter() - ta) * 1e3 / K
+    two_call_ms = timed(two_call_step, K)
+    restore()
+    for ci in range(copies):
+        check(lib.sparq_kv_append(*table[ci][0][0]["append"]))           # lengths S_b, as in the first timed step
+    dec_avg_ms = timed_events(lambda i: check(lib.sparq_decode(*table[i % copies][0][i % n_pool]["decode"])), K)
+    restore()
+    append_ms = timed(lambda i: check(lib.sparq_kv_append(*table[i % copies][0][i % n_pool]["append"])), K)
+    restore()
 
-    # algorithmic bytes of one decode launch at the lengths used above (first visit of each copy: S_b)
+    # algorithmic bytes of the K timed launches: copy c is visited at steps c, c + copies, ... and holds
+    # S_b + (visit number) rows when it is decoded
     tot = {"stage1": 0, "stage3": 0, "blend": 0, "total": 0}
+    kk = None if kps is None else kps.tolist()
     for i in range(K):
-        kk = None if kps is None else kps.tolist()
-        bts = T.sparq_decode_bytes(seq0.tolist(), w.H, w.d_h, w.r, w.k, e, kk)
+        bts = T.sparq_decode_bytes((seq0 + (i // copies)).tolist(), w.H, w.d_h, w.r, w.k, e, kk)
         for key in tot:
             tot[key] += bts[key]
     dec_bytes = tot["total"] / K
     app_bytes = T.kv_append_bytes(w.B, w.H_kv, w.d_h, e)
-    achieved = dec_bytes / (dec_avg_ms * 1e-3) / 1e9
+    dec_bytes0 = T.sparq_decode_bytes(seq0.tolist(), w.H, w.d_h, w.r, w.k, e, kk)["total"]
+    achieved = (dec_bytes + app_bytes) / (step_avg_ms * 1e-3) / 1e9
 
     # ---- in-library dense decode on the same rotation ----
     dense = {}
     if not args.no_dense:
+        dense_fn = lambda i: check(lib.dense_decode(*table[i % copies][0][i % n_pool]["dense"]))
         for i in range(min(Wm, 5)):
-            lib.dense_decode(*den_args[i % n_args])
-        torch.cuda.synchronize(); td = time.perf_counter()
-        nd = max(10, K // 4)
-        for i in range(nd):
-            lib.dense_decode(*den_args[i % n_args])
-        torch.cuda.synchronize(); dense_ms = (time.perf_counter() - td) * 1e3 / nd
+            dense_fn(i)
+        dense_ms = timed(dense_fn, max(10, K // 4))
         dbytes = T.dense_decode_bytes(seq0.tolist(), w.H, w.H_kv, w.d_h, e)
         dense = {"dense_ms_per_step": round(dense_ms, 4), "dense_GBps": round(dbytes / dense_ms / 1e6, 1),
                  "dense_frac_of_peak": round(dbytes / dense_ms / 1e6 / HBM_PEAK_GBS, 4),
@@ -219,7 +235,7 @@ def main():
         import numpy as np
         restore()
         c = caches[0]
-        c.append(kn_pool[0], vn_pool[0]); torch.cuda.synchronize()
+        c.append(kn_pool[0], vn_pool[0]); torch.cuda.synchronize()       # vm[0][0], sl[0][0] are c's own buffers
         # sample: the first n_b sequences of the batch (all heads), sized for roughly cpu-seconds of work
         n_b = w.B
         Kh = W.to_codes(c.K[:n_b]); Vh = W.to_codes(c.V[:n_b]); qh = W.to_codes(q_pool[0][:n_b])
@@ -245,17 +261,18 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "B": w.B, "H": w.H, "H_kv": w.H_kv, "d_h": w.d_h, "S": int(seq0.max()),
                    "r": w.r, "k": w.k if kps is None else "ceil(S_b/%d)" % w.k_div, "cache_dtype": w.dtype,
-                   "step": "sparq_kv_append + sparq_decode", "cache_copies_rotated": copies, "q_pool": n_pool,
-                   "S_max": S_max},
+                   "step": "sparq_decode_step (append + decode in one launch)", "cache_copies_rotated": copies,
+                   "q_pool": n_pool, "S_max": S_max},
         "step_GBps": round((dec_bytes + app_bytes) / ms_per_step / 1e6, 1),
         "step_frac_of_peak": round((dec_bytes + app_bytes) / ms_per_step / 1e6 / HBM_PEAK_GBS, 4),
-        "append_ms": round(append_ms, 5),
+        "two_launch_step_ms": round(two_call_ms, 5), "decode_launch_ms": round(dec_avg_ms, 5),
+        "decode_launch_GBps": round(dec_bytes0 / dec_avg_ms / 1e6, 1), "append_launch_ms": round(append_ms, 5),
         "hbm_probe": probe,
-        "roofline": {"kernel": "sparq_decode_fused", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic_from_profile(args.workload),
-                     "algorithmic_bytes_per_launch": int(dec_bytes), "avg_launch_ms": round(dec_avg_ms, 5),
-                     "isolated_launch_ms_median": round(dec_ms[K // 2], 5),
-                     "stage_bytes": {k2: int(v / K) for k2, v in tot.items()}},
+        "roofline": {"kernel": "sparq_decode_fused<APPEND> (sparq_decode_step)", "bound": "hbm",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic_from_profile(args.workload),
+                     "algorithmic_bytes_per_launch": int(dec_bytes + app_bytes), "avg_launch_ms": round(step_avg_ms, 5),
+                     "stage_bytes": dict({k2: int(v / K) for k2, v in tot.items() if k2 != "total"}, append=app_bytes)},
         "cpu_baseline": cpu,
     }
     rec.update(dense)

@@ -124,6 +124,23 @@ int sparq_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
                  size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The whole decode step in one launch: exactly sparq_kv_append with n_new = 1 followed by
+ * sparq_decode (Section 4: the step writes k and v, updates the mean value vector and attends
+ * over the cache including the new token), except that the small state is not updated in place:
+ * the new lengths and means are written to seq_lens_next [B] and v_mean_next [B, H_kv, d_h]
+ * (device, must not alias cache->seq_lens / cache->v_mean, which are only read) and the caller
+ * swaps the two pairs of buffers between steps.  K, V and Kt receive row S_b in place.  The new
+ * row is taken from k_new / v_new [B, H_kv, d_h] by every head, so no head depends on another
+ * one's write.  A sequence with S_b = S_max is decoded without the new row, keeps its length
+ * and mean, and raises SPARQ_ERR_APPEND_FULL.  Other arguments as for sparq_decode.
+ */
+int sparq_decode_step(const sparq_shape* shape, const sparq_cache* cache, const void* k_new,
+                      const void* v_new, float* v_mean_next, int32_t* seq_lens_next, const void* q,
+                      const int32_t* k_per_seq, void* out, float* alpha_out, int32_t* idx_out,
+                      int32_t idx_stride, int32_t* chan_out, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
+/*
  * Dense single-query attention y = softmax(q K^T / sqrt(d_h)) V over rows 0..S_b-1
  * (Section 3, Eq. 1): the in-library comparison.  Reads K and V once per KV head for
  * all g query heads of the group.  Uses the workspace for split-sequence partials.

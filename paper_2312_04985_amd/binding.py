@@ -20,7 +20,7 @@ SPARQ_FLAG_NO_REALLOC, SPARQ_FLAG_GQA_SHARED = 1, 2
 SPARQ_ERR_APPEND_FULL, SPARQ_ERR_EMPTY_SEQ, SPARQ_ERR_IDX_TRUNCATED, SPARQ_ERR_BAD_SEQ_LEN = 1, 2, 4, 8
 SPARQ_OK, SPARQ_EINVAL, SPARQ_EUNSUPPORTED, SPARQ_EWORKSPACE, SPARQ_ELAUNCH = 0, -1, -2, -3, -4
 
-EXPORTS = ["sparq_workspace_bytes", "sparq_workspace_init", "sparq_kv_append", "sparq_decode",
+EXPORTS = ["sparq_workspace_bytes", "sparq_workspace_init", "sparq_kv_append", "sparq_decode", "sparq_decode_step",
            "dense_decode", "sparq_async_error", "sparq_copy_probe", "sparq_read_probe", "sparq_status_string"]
 
 
@@ -59,6 +59,7 @@ def load() -> ctypes.CDLL:
     L.sparq_workspace_init.argtypes = [vp, sz, vp]
     L.sparq_kv_append.argtypes = [shp, cch, vp, vp, i32, vp, vp, sz, vp]
     L.sparq_decode.argtypes = [shp, cch, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+    L.sparq_decode_step.argtypes = [shp, cch, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     L.dense_decode.argtypes = [shp, cch, vp, vp, vp, sz, vp]
     L.sparq_async_error.argtypes = [vp, ctypes.POINTER(i32), vp]
     L.sparq_copy_probe.argtypes = [vp, vp, sz, vp]
@@ -137,6 +138,20 @@ def sparq_decode(shape, cache, q, k_per_seq, out, alpha_out, idx_out, chan_out, 
                                idx_stride, _dev(chan_out, "chan_out", torch.int32),
                                _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                _stream(stream)))
+
+
+def sparq_decode_step(shape, cache, k_new, v_new, v_mean_next, seq_lens_next, q, k_per_seq, out, alpha_out,
+                      idx_out, chan_out, workspace, stream=None) -> None:
+    idx_stride = 0 if idx_out is None else idx_out.shape[-1]
+    _check("sparq_decode_step",
+           load().sparq_decode_step(ctypes.byref(shape), ctypes.byref(cache), _dev(k_new, "k_new"), _dev(v_new, "v_new"),
+                                    _dev(v_mean_next, "v_mean_next", torch.float32),
+                                    _dev(seq_lens_next, "seq_lens_next", torch.int32), _dev(q, "q"),
+                                    _dev(k_per_seq, "k_per_seq", torch.int32), _dev(out, "out"),
+                                    _dev(alpha_out, "alpha_out", torch.float32), _dev(idx_out, "idx_out", torch.int32),
+                                    idx_stride, _dev(chan_out, "chan_out", torch.int32),
+                                    _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                    _stream(stream)))
 
 
 def dense_decode(shape, cache, q, out, workspace, stream=None) -> None:

@@ -30,6 +30,8 @@ class DecodeCache:
         self.workspace = torch.empty((B.sparq_workspace_bytes(self.shape),), dtype=torch.uint8, device=self.device)
         B.sparq_workspace_init(self.workspace)
         self.cache = B.make_cache(self.K, self.Kt, self.V, self.v_mean, self.seq_lens)
+        self._v_mean_alt = None      # second (v_mean, seq_lens) pair for the one-launch step, made on first use
+        self._seq_lens_alt = None
 
     def with_params(self, r: int, k: int, flags: int = 0):
         """The same buffers seen through another (r, k, flags) setting."""
@@ -54,6 +56,27 @@ class DecodeCache:
         chan = torch.empty((self.B, self.H, self.r), dtype=torch.int32, device=self.device)
         B.sparq_decode(self.shape, self.cache, q, k_per_seq, out, alpha, idx, chan, self.workspace, stream)
         return out, alpha, idx, chan
+
+    def step(self, k_new: torch.Tensor, v_new: torch.Tensor, q: torch.Tensor, k_per_seq: Optional[torch.Tensor] = None,
+             aux: bool = False, idx_stride: Optional[int] = None, out: Optional[torch.Tensor] = None, stream=None):
+        """Append one row and decode in one launch (sparq_decode_step); the (v_mean, seq_lens) pair that
+        the call wrote becomes the current one."""
+        if self._v_mean_alt is None:
+            self._v_mean_alt = torch.empty_like(self.v_mean)
+            self._seq_lens_alt = torch.empty_like(self.seq_lens)
+        out = torch.empty((self.B, self.H, self.d_h), dtype=self.dtype, device=self.device) if out is None else out
+        alpha = idx = chan = None
+        if aux:
+            stride = idx_stride if idx_stride is not None else min(self.k, self.S_max)
+            alpha = torch.empty((self.B, self.H), dtype=torch.float32, device=self.device)
+            idx = torch.empty((self.B, self.H, stride), dtype=torch.int32, device=self.device)
+            chan = torch.empty((self.B, self.H, self.r), dtype=torch.int32, device=self.device)
+        B.sparq_decode_step(self.shape, self.cache, k_new, v_new, self._v_mean_alt, self._seq_lens_alt, q, k_per_seq,
+                            out, alpha, idx, chan, self.workspace, stream)
+        self.v_mean, self._v_mean_alt = self._v_mean_alt, self.v_mean
+        self.seq_lens, self._seq_lens_alt = self._seq_lens_alt, self.seq_lens
+        self.cache = B.make_cache(self.K, self.Kt, self.V, self.v_mean, self.seq_lens)
+        return (out, alpha, idx, chan) if aux else out
 
     def dense(self, q: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None):
         out = torch.empty((self.B, self.H, self.d_h), dtype=self.dtype, device=self.device) if out is None else out

@@ -119,6 +119,34 @@ int sparq_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
   DecodeArgs a;
   a.K = cache->K; a.Kt = cache->Kt; a.V = cache->V; a.v_mean = cache->v_mean; a.seq_lens = cache->seq_lens;
   a.q = q; a.k_per_seq = k_per_seq; a.out = out; a.alpha_out = alpha_out; a.idx_out = idx_out;
+  a.k_new = nullptr; a.v_new = nullptr; a.v_mean_next = nullptr; a.seq_lens_next = nullptr;
+  a.chan_out = chan_out; a.err = static_cast<int32_t*>(workspace);
+  a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h;
+  a.r = shape->r; a.k = shape->k; a.idx_stride = idx_out ? idx_stride : 0; a.flags = shape->flags;
+  return launch_decode(a, shape->dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
+}
+
+int sparq_decode_step(const sparq_shape* shape, const sparq_cache* cache, const void* k_new,
+                      const void* v_new, float* v_mean_next, int32_t* seq_lens_next, const void* q,
+                      const int32_t* k_per_seq, void* out, float* alpha_out, int32_t* idx_out,
+                      int32_t idx_stride, int32_t* chan_out, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
+  int rc = check_shape(shape);
+  if (rc == SPARQ_OK) rc = check_cache(cache);
+  if (rc != SPARQ_OK) return rc;
+  if (!q || !out || !aligned16(q) || !aligned16(out)) return SPARQ_EINVAL;
+  if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)) return SPARQ_EINVAL;
+  if (!v_mean_next || !seq_lens_next || !aligned16(v_mean_next)) return SPARQ_EINVAL;
+  if (v_mean_next == cache->v_mean || seq_lens_next == cache->seq_lens) return SPARQ_EINVAL;
+  if (idx_out && idx_stride < 1) return SPARQ_EINVAL;
+  rc = check_workspace(shape, workspace, workspace_bytes);
+  if (rc != SPARQ_OK) return rc;
+  if (shape->flags & SPARQ_FLAG_GQA_SHARED) return SPARQ_EUNSUPPORTED;
+  if (decode_lds_bytes(shape->S_max, shape->d_h) > (size_t)max_lds_bytes()) return SPARQ_EUNSUPPORTED;
+  DecodeArgs a;
+  a.K = cache->K; a.Kt = cache->Kt; a.V = cache->V; a.v_mean = cache->v_mean; a.seq_lens = cache->seq_lens;
+  a.q = q; a.k_per_seq = k_per_seq; a.out = out; a.alpha_out = alpha_out; a.idx_out = idx_out;
+  a.k_new = k_new; a.v_new = v_new; a.v_mean_next = v_mean_next; a.seq_lens_next = seq_lens_next;
   a.chan_out = chan_out; a.err = static_cast<int32_t*>(workspace);
   a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h;
   a.r = shape->r; a.k = shape->k; a.idx_stride = idx_out ? idx_stride : 0; a.flags = shape->flags;

@@ -12,8 +12,11 @@ constexpr int kWorkspaceHeader = 256;   // bytes; word 0 is the error word
 constexpr int kProbeBlocks = 256 * 8;   // workgroups (of 256 threads) of the bandwidth probes
 
 struct DecodeArgs {
-  const void* K; const void* Kt; const void* V; const float* v_mean; const int32_t* seq_lens;
+  void* K; void* Kt; void* V;                  // written only by the fused-append variant
+  const float* v_mean; const int32_t* seq_lens;
   const void* q; const int32_t* k_per_seq;
+  const void* k_new; const void* v_new;          // non-null: fused append (one-launch decode step)
+  float* v_mean_next; int32_t* seq_lens_next;
   void* out; float* alpha_out; int32_t* idx_out; int32_t* chan_out; int32_t* err;
   int32_t B, H, H_kv, S_max, d_h, r, k, idx_stride;
   uint32_t flags;

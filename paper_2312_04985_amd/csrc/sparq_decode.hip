@@ -31,6 +31,8 @@ struct Lds {
   float* red;       // [32]
   uint32_t* wcnt;   // [2][NW] double-buffered wave totals of the workgroup scan
   int* ctl;         // [8]
+  uint16_t* knew;   // [DH] codes of the key row being appended (fused append only)
+  uint16_t* vnew;   // [DH]
 };
 
 template <int DH>
@@ -45,7 +47,9 @@ __device__ __forceinline__ Lds carve(uint32_t* base, int S_max) {
   l.mag = base; base += DH;
   l.red = reinterpret_cast<float*>(base); base += 32;
   l.wcnt = base; base += 16;
-  l.ctl = reinterpret_cast<int*>(base);
+  l.ctl = reinterpret_cast<int*>(base); base += 8;
+  l.knew = reinterpret_cast<uint16_t*>(base); base += DH / 2;
+  l.vnew = reinterpret_cast<uint16_t*>(base);
   return l;
 }
 
@@ -102,7 +106,12 @@ __device__ __forceinline__ void find_threshold_bin(const uint32_t* hist, int nee
 #define TL_MARK(slot) do {} while (0)
 #endif
 
-template <class T, int DH>
+// APPEND = true is the one-launch decode step: the new key/value row of every KV head (k_new, v_new)
+// counts as position S_b of its sequence without being read back from the cache.  Every workgroup
+// takes that row from the inputs; the workgroup of the first query head of a KV group also writes
+// it into K, V and Kt and stores the updated mean; lengths and means go to the *_next buffers, so
+// no workgroup can observe another one's update of the state it reads.
+template <class T, int DH, bool APPEND>
 __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) {
   extern __shared__ __align__(16) uint32_t smem[];
   const Lds L = carve<DH>(smem, a.S_max);
@@ -124,13 +133,26 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   const int hk = h / (a.H / a.H_kv);
   const size_t kv_head = (size_t)b * a.H_kv + hk;
 
-  uint16_t qcode = 0;
-  if (tid < DH) qcode = reinterpret_cast<const uint16_t*>(a.q)[(size_t)u * DH + tid];
+  uint16_t qcode = 0, kcode = 0, vcode = 0;
+  if (tid < DH) {
+    qcode = reinterpret_cast<const uint16_t*>(a.q)[(size_t)u * DH + tid];
+    if (APPEND) {
+      kcode = reinterpret_cast<const uint16_t*>(a.k_new)[kv_head * DH + tid];
+      vcode = reinterpret_cast<const uint16_t*>(a.v_new)[kv_head * DH + tid];
+    }
+  }
   int S = a.seq_lens[b];
   TL_MARK(15);
   if (S < 0 || S > a.S_max) {
     if (tid == 0) atomicOr(a.err, 8);
     S = S < 0 ? 0 : a.S_max;
+  }
+  bool appended = false;                          // this sequence takes the new row (uniform)
+  const bool owner = APPEND && h == hk * (a.H / a.H_kv);   // writes the row and the new mean
+  if (APPEND) {
+    if (S + 1 <= a.S_max) { appended = true; S += 1; }
+    else if (tid == 0) atomicOr(a.err, 1);
+    if (h == 0 && tid == 0) a.seq_lens_next[b] = S;
   }
   int kb = a.k_per_seq ? a.k_per_seq[b] : a.k;
   if (kb < 1) kb = 1;
@@ -142,6 +164,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
     if (tid == 0) { atomicOr(a.err, 2); if (a.alpha_out) a.alpha_out[u] = 0.0f; }
     if (a.chan_out && tid < a.r) a.chan_out[(size_t)u * a.r + tid] = -1;
     if (a.idx_out) for (int n = tid; n < a.idx_stride; n += NT) a.idx_out[(size_t)u * a.idx_stride + n] = -1;
+    if (owner && tid < DH) a.v_mean_next[kv_head * DH + tid] = a.v_mean[kv_head * DH + tid];
     return;
   }
 
@@ -152,6 +175,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   if (tid < DH) {
     L.mag[tid] = ((uint32_t)(qcode & 0x7fffu) << 9) | (uint32_t)(511 - tid);
     L.qf[tid] = T::widen(qcode);
+    if (APPEND) { L.knew[tid] = kcode; L.vnew[tid] = vcode; }
   }
   __syncthreads();
   TL_MARK(13);
@@ -204,6 +228,13 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   }
   __syncthreads();
   if (a.chan_out && tid < a.r) a.chan_out[(size_t)u * a.r + tid] = L.chan[tid];
+  float dot_new = 0.0f;   // approximate logit numerator of the appended row (every wave computes it)
+  if (APPEND && appended) {
+    float part_new = 0.0f;
+    for (int jj = lane; jj < ((a.r + 7) & ~7); jj += kWave)
+      part_new = fmaf(T::widen(L.knew[L.chan[jj]]), L.qs[jj], part_new);
+    dot_new = wave_sum(part_new);
+  }
   TL_MARK(1);
 
   // ---------------- stage 1: approximate logits over the r selected channel rows ----------------
@@ -233,41 +264,59 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
       for (int e = 0; e < 8; ++e) acc[e] = fmaf(f[e], qv, acc[e]);
     }
   };
-  for (int c = tid; c < n_chunks; c += NT) {
+  // The (chunk, batch) pairs a thread owns form one flat sequence that runs through a two-deep
+  // software pipeline: a batch of 8 loads is always in flight behind the one being accumulated,
+  // also across chunk boundaries, so a short last sweep costs no extra memory round trip.
+  {
+    const int my_chunks = n_chunks > tid ? (n_chunks - tid + NT - 1) / NT : 0;
+    const int items = my_chunks * n_batches;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const uint32_t voff = (uint32_t)c * 16u;
-    uint4 va[8], vb[8];
-    // software pipeline over the batches: one batch of 8 loads is always in flight behind the
-    // one being accumulated
-    issue(va, voff, 0);
-    int bi = 0;
-    for (; bi + 2 < n_batches; bi += 2) {
-      issue(vb, voff, bi + 1);
-      consume(va, acc, bi);
-      issue(va, voff, bi + 2);
-      consume(vb, acc, bi + 1);
-    }
-    if (bi + 1 < n_batches) {
-      issue(vb, voff, bi + 1);
-      consume(va, acc, bi);
-      consume(vb, acc, bi + 1);
-    } else {
-      consume(va, acc, bi);
-    }
-    uint32_t kx[8];
+    int ic = 0, ib = 0, cc = 0, cb = 0;   // issue and consume cursors: (own chunk number, batch)
+    auto issue_next = [&](uint4 (&v)[8]) {
+      issue(v, (uint32_t)(tid + ic * NT) * 16u, ib);
+      if (++ib == n_batches) { ib = 0; ++ic; }
+    };
+    auto consume_next = [&](const uint4 (&v)[8]) {
+      consume(v, acc, cb);
+      if (++cb == n_batches) {          // chunk finished: keys to LDS and into the first histogram
+        const int c = tid + cc * NT;
+        uint32_t kx[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      if (c * 8 + e < S) {
-        tmax = fmaxf(tmax, acc[e]);
-        kx[e] = float_to_key(acc[e]);
-        atomicAdd(&L.hist[hist_slot(kx[e] >> 21)], 1u);
+        for (int e = 0; e < 8; ++e) {
+          if (c * 8 + e < S) {
+            const float val = (APPEND && appended && c * 8 + e == S - 1) ? dot_new : acc[e];
+            tmax = fmaxf(tmax, val);
+            kx[e] = float_to_key(val);
+            atomicAdd(&L.hist[hist_slot(kx[e] >> 21)], 1u);
+          } else {
+            kx[e] = 0u;
+          }
+          acc[e] = 0.0f;
+        }
+        uint4* dst = reinterpret_cast<uint4*>(L.keys + c * 8);
+        dst[0] = make_uint4(kx[0], kx[1], kx[2], kx[3]);
+        dst[1] = make_uint4(kx[4], kx[5], kx[6], kx[7]);
+        cb = 0; ++cc;
+      }
+    };
+    uint4 va[8], vb[8];
+    if (items > 0) {
+      issue_next(va);
+      int i = 0;
+      for (; i + 2 < items; i += 2) {
+        issue_next(vb);
+        consume_next(va);
+        issue_next(va);
+        consume_next(vb);
+      }
+      if (i + 1 < items) {
+        issue_next(vb);
+        consume_next(va);
+        consume_next(vb);
       } else {
-        kx[e] = 0u;
+        consume_next(va);
       }
     }
-    uint4* dst = reinterpret_cast<uint4*>(L.keys + c * 8);
-    dst[0] = make_uint4(kx[0], kx[1], kx[2], kx[3]);
-    dst[1] = make_uint4(kx[4], kx[5], kx[6], kx[7]);
   }
   tmax = wave_max(tmax);
   if (lane == 0) L.red[wave] = tmax;
@@ -408,6 +457,8 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   constexpr int GROUP = RPI * UNR;          // rows the workgroup covers per group of loads
   const int n_groups = (kq + GROUP - 1) / GROUP;
+  // positions are ascending, so the appended row (position S - 1) can only be the last entry
+  const bool new_selected = APPEND && appended && pos[kq - 1] == S - 1;
   auto issue3 = [&](uint4 (&kr)[UNR], uint4 (&vr)[UNR], int g) {
 #pragma unroll
     for (int t = 0; t < UNR; ++t) {
@@ -421,7 +472,10 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
 #pragma unroll
     for (int t = 0; t < UNR; ++t) {
       float f[8];
-      unpack8<T>(kr[t], f);
+      const bool from_inputs = APPEND && new_selected && (g * GROUP + t * RPI + slot == kq - 1);
+      const uint4 kt = from_inputs ? *reinterpret_cast<const uint4*>(L.knew + sub * 8) : kr[t];
+      const uint4 vt = from_inputs ? *reinterpret_cast<const uint4*>(L.vnew + sub * 8) : vr[t];
+      unpack8<T>(kt, f);
       float dot = 0.0f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) dot = fmaf(f[e], q8[e], dot);
@@ -429,7 +483,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
       if (g * GROUP + t * RPI + slot < kq) {
         const float m_new = fmaxf(m_run, dot);
         const float sc = exp2f(m_run - m_new), pr = exp2f(dot - m_new);
-        unpack8<T>(vr[t], f);
+        unpack8<T>(vt, f);
         l_run = l_run * sc + pr;
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] = acc[e] * sc + pr * f[e];
@@ -485,17 +539,32 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
       y3 += L.part[w * (DH + 2) + tid] * s;
     }
     y3 /= l_all;
+    float vm = a.v_mean[kv_head * DH + tid];
+    if (APPEND) {
+      if (appended) vm += (T::widen(L.vnew[tid]) - vm) * (1.0f / (float)S);   // same update as append_one_row
+      if (owner) a.v_mean_next[kv_head * DH + tid] = vm;
+    }
     float y = y3;
-    if (!(a.flags & 1u)) y = alpha * y3 + (1.0f - alpha) * a.v_mean[kv_head * DH + tid];
+    if (!(a.flags & 1u)) y = alpha * y3 + (1.0f - alpha) * vm;
     out[tid] = T::narrow(y);
+  }
+  if (APPEND && owner && appended) {
+    // the row into both key layouts and the value cache
+    uint16_t* Krow = reinterpret_cast<uint16_t*>(a.K) + (kv_head * a.S_max + (S - 1)) * DH;
+    uint16_t* Vrow = reinterpret_cast<uint16_t*>(a.V) + (kv_head * a.S_max + (S - 1)) * DH;
+    if (tid < DH / 8) {
+      reinterpret_cast<uint4*>(Krow)[tid] = reinterpret_cast<const uint4*>(L.knew)[tid];
+      reinterpret_cast<uint4*>(Vrow)[tid] = reinterpret_cast<const uint4*>(L.vnew)[tid];
+    }
+    if (tid < DH) reinterpret_cast<uint16_t*>(a.Kt)[(kv_head * DH + tid) * a.S_max + (S - 1)] = L.knew[tid];
   }
   TL_MARK(5);
 }
 
-template <class T, int DH>
+template <class T, int DH, bool APPEND>
 hipError_t launch_one(const DecodeArgs& a, hipStream_t s) {
   const size_t lds = decode_lds_bytes(a.S_max, DH);
-  auto kern = sparq_decode_fused<T, DH>;
+  auto kern = sparq_decode_fused<T, DH, APPEND>;
   if (lds > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -508,17 +577,22 @@ hipError_t launch_one(const DecodeArgs& a, hipStream_t s) {
 }  // namespace
 
 size_t decode_lds_bytes(int S_max, int d_h) {
-  return 4 * ((size_t)S_max + 2 * kRadixBins + (size_t)NW * (d_h + 2) + 4 * (size_t)d_h + 32 + 16 + 8);
+  return 4 * ((size_t)S_max + 2 * kRadixBins + (size_t)NW * (d_h + 2) + 5 * (size_t)d_h + 32 + 16 + 8);
+}
+
+template <bool APPEND>
+hipError_t launch_any(const DecodeArgs& a, int dtype, hipStream_t s) {
+  const bool bf = dtype == 1;
+  switch (a.d_h) {
+    case 64:  return bf ? launch_one<BF16, 64, APPEND>(a, s) : launch_one<F16, 64, APPEND>(a, s);
+    case 128: return bf ? launch_one<BF16, 128, APPEND>(a, s) : launch_one<F16, 128, APPEND>(a, s);
+    case 256: return bf ? launch_one<BF16, 256, APPEND>(a, s) : launch_one<F16, 256, APPEND>(a, s);
+    default:  return hipErrorInvalidValue;
+  }
 }
 
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s) {
-  const bool bf = dtype == 1;
-  switch (a.d_h) {
-    case 64:  return bf ? launch_one<BF16, 64>(a, s) : launch_one<F16, 64>(a, s);
-    case 128: return bf ? launch_one<BF16, 128>(a, s) : launch_one<F16, 128>(a, s);
-    case 256: return bf ? launch_one<BF16, 256>(a, s) : launch_one<F16, 256>(a, s);
-    default:  return hipErrorInvalidValue;
-  }
+  return a.k_new ? launch_any<true>(a, dtype, s) : launch_any<false>(a, dtype, s);
 }
 
 }  // namespace sparq

@@ -190,3 +190,68 @@ def test_unsupported_requests_are_refused():
     assert e.value.status == B.SPARQ_EUNSUPPORTED
     with pytest.raises(ValueError):
         b.cache.with_params(16, 8).decode(q.cpu())
+
+
+# ------------------------------------------------------------------ the one-launch decode step
+
+@pytest.mark.parametrize("name,kw", [
+    ("mha_f16", dict(B=3, H=4, H_kv=4, d_h=128, S=700, r=16, k=64, dtype="f16")),
+    ("gqa_bf16", dict(B=2, H=8, H_kv=2, d_h=128, S=4100, r=32, k=512, dtype="bf16")),
+    ("d256", dict(B=2, H=2, H_kv=2, d_h=256, S=1500, r=64, k=200, dtype="bf16")),
+    ("d64_k_ge_s", dict(B=2, H=4, H_kv=2, d_h=64, S=40, r=8, k=64, dtype="f16")),
+])
+def test_decode_step_equals_append_then_decode(name, kw):
+    """sparq_decode_step must leave exactly the state, and return exactly the outputs, of
+    sparq_kv_append followed by sparq_decode, over several consecutive steps; and both match the
+    oracle.  Lengths are ragged so the new row lands in different chunk positions."""
+    w = W.Workload(name, seed=31, **kw)
+    seq = torch.tensor([max(1, w.S - 13 * i) for i in range(w.B)], dtype=torch.int32)
+    steps = 5
+    S_max = W.round_up(w.S + steps, 64)
+    a = Hn.build_cache(w, seq_lens=seq, S_max=S_max, v_offset=True)     # separate calls
+    f = Hn.build_cache(w, seq_lens=seq, S_max=S_max, v_offset=True)     # fused step
+    kn, vn = W.draw_kv(W.scaled(w, seed=77), "cuda", n_rows=steps, v_offset=True)
+    cur = seq.clone()
+    for t in range(steps):
+        k_t, v_t = kn[:, :, t].contiguous(), vn[:, :, t].contiguous()
+        # queries planted on rows that are already cached
+        q = W.draw_queries(w, a.cache.K, cur, n=1, q_scale=0.02, stream=t)[0]
+        if t == 2:          # make the new row the best match for head 0 so it is certainly selected
+            q[:, 0] = (k_t[:, 0].float() * 0.05).to(q.dtype)
+        a.cache.append(k_t, v_t)
+        o1, al1, i1, c1 = a.cache.decode(q, aux=True)
+        o2, al2, i2, c2 = f.cache.step(k_t, v_t, q, aux=True)
+        torch.cuda.synchronize()
+        cur = cur + 1
+        assert a.cache.error_flags() == 0 and f.cache.error_flags() == 0
+        assert f.cache.seq_lens.cpu().tolist() == cur.tolist() == a.cache.seq_lens.cpu().tolist()
+        assert torch.equal(i1, i2) and torch.equal(c1, c2), f"selection differs at step {t}"
+        # the new row's approximate logit is summed in a different order in the two paths (one fp32
+        # ulp), so alpha and the output may differ in the last place, nothing more
+        assert (al1 - al2).abs().max().item() <= 1e-6
+        assert ((o1.float() - o2.float()).abs() <= 2.0 ** -7 * o1.float().abs() + 1e-6).all(), f"output differs at step {t}"
+        assert torch.equal(a.cache.v_mean, f.cache.v_mean), "running mean differs"
+        for bi in range(w.B):
+            s = int(cur[bi])
+            assert torch.equal(a.cache.K[bi, :, :s], f.cache.K[bi, :, :s]) and torch.equal(a.cache.V[bi, :, :s], f.cache.V[bi, :, :s])
+            assert torch.equal(a.cache.Kt[bi, :, :, :s], f.cache.Kt[bi, :, :, :s])
+        if t == 2:
+            assert all(int(i2[bi, 0][i2[bi, 0] >= 0].max()) == int(cur[bi]) - 1 for bi in range(w.B)), "new row not selected"
+    # the fused path's final state against the oracle
+    fb = Hn.Built(w, f.cache, f.cache.K[:, :, :int(cur.max())].clone(), f.cache.V[:, :, :int(cur.max())].clone(), cur, None)
+    say(Hn.compare_decode(fb, q))
+
+
+def test_decode_step_on_a_full_sequence():
+    w = W.Workload("step_full", 2, 2, 2, 128, 64, 16, 8, "f16", seed=32)
+    b = Hn.build_cache(w, seq_lens=torch.tensor([64, 30], dtype=torch.int32), S_max=64)
+    kn, vn = W.draw_kv(W.scaled(w, seed=78), "cuda", n_rows=1)
+    q = W.draw_queries(w, b.K_src, b.seq_lens)[0]
+    ref = b.cache.decode(q)                                  # sequence 0 must decode as if nothing was appended
+    vm0 = b.cache.v_mean.clone()
+    out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q)
+    torch.cuda.synchronize()
+    assert b.cache.error_flags() == B.SPARQ_ERR_APPEND_FULL
+    assert b.cache.seq_lens.cpu().tolist() == [64, 31]
+    assert torch.equal(out[0].view(torch.int16), ref[0].view(torch.int16)) and torch.equal(b.cache.v_mean[0], vm0[0])
+    assert torch.equal(b.cache.K[1, :, 30], kn[1, :, 0]) and torch.equal(b.cache.Kt[1, :, :, 30], kn[1, :, 0])
