@@ -1,0 +1,421 @@
+// The stages of the SparQ decode step (Section 4, Steps 1-3) as workgroup-level device functions.
+// They are shared by the one-workgroup-per-head kernel (sparq_decode.hip) and by the
+// split-sequence kernels for few heads and long sequences (sparq_decode_split.hip).
+// All functions are called by all kDecodeThreads threads of a workgroup (they contain barriers).
+#pragma once
+#include "common.h"
+#include "params.h"
+
+namespace sparq {
+
+constexpr int NT = kDecodeThreads;
+constexpr int NW = NT / kWave;   // waves per workgroup
+
+// ------------------------------------------------------------------------------------------------
+// small workgroup primitives
+
+// Exclusive prefix sum of v over the workgroup in thread order; *total gets the sum.
+// One barrier; callers alternate `wsum` between two NW-word buffers on consecutive calls.
+__device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wsum, int lane, int wave,
+                                                    uint32_t* total) {
+  const uint32_t incl = wave_scan_incl(v);
+  if (lane == kWave - 1) wsum[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    const uint32_t t = wsum[w];
+    if (w < wave) before += t;
+    all += t;
+  }
+  *total = all;
+  return before + incl - v;
+}
+
+// Histogram bins are stored swizzled so that the 32 consecutive digits a lane sums in
+// find_threshold_bin sit in 32 different rows of 64 words: lane-consecutive, conflict-free reads.
+__device__ __forceinline__ uint32_t hist_slot(uint32_t digit) { return ((digit & 31u) << 6) | (digit >> 5); }
+
+// One wave locates the digit at which the count taken from the top digit downwards reaches `need`;
+// writes {digit, how many keys of that digit are needed, keys with that digit} to ctl[0..2].
+// Two levels: lane l sums digits 32l..32l+31 and a wave scan finds the lane, then the 32 digits of
+// that lane are scanned across lanes.  Requires 1 <= need <= total count.
+__device__ __forceinline__ void find_threshold_bin(const uint32_t* hist, int need, int lane, int* ctl) {
+  uint32_t mine = 0;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) mine += hist[(i << 6) | lane];
+  const uint32_t incl = wave_scan_incl(mine);
+  const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
+  const uint32_t above = total - incl;      // keys with digits owned by higher lanes
+  const uint64_t hit = __ballot(above < (uint32_t)need && (uint32_t)need <= above + mine);
+  const int ls = hit ? __ffsll((unsigned long long)hit) - 1 : 0;
+  const uint32_t need2 = (uint32_t)need - (uint32_t)__shfl((int)above, ls);
+  // lane t < 32 takes digit 32*ls + 31 - t, so that the scan runs from the top digit down
+  const uint32_t c = lane < 32 ? hist[((31 - lane) << 6) | ls] : 0u;
+  const uint32_t inc2 = wave_scan_incl(c);
+  if (lane < 32 && (inc2 - c) < need2 && need2 <= inc2) {
+    ctl[0] = ls * 32 + 31 - lane; ctl[1] = (int)(need2 - (inc2 - c)); ctl[2] = (int)c;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Step 1a: the r largest components of |q| (ties to the lower channel) and the temperature (Eq. 7)
+
+struct QueryLds {
+  uint32_t* mag;   // [DH] sort keys
+  int* rankp;      // [NT] partial ranks
+  float* qf;       // [DH] query as fp32
+  float* qs;       // [DH] selected query components, channel-ascending, padded to a multiple of 8
+  int* chan;       // [DH] selected channels, ascending, same padding
+};
+
+// Channel j gets the sort key (|q_j| as its 15-bit code) << 9 | (511 - j): keys are distinct and
+// "larger key" is exactly "larger magnitude, or equal magnitude and lower channel"; the rank of a
+// channel is the number of larger keys and the NT threads split the DH x DH comparisons.  Every
+// wave then finishes the selection for all channels by itself (ranks, ballots, L1 sums), wave g
+// writing the list entries of channels 64g..64g+63.  The list is padded to a multiple of 8 with the
+// last channel at weight 0, so that Step 1b works on whole batches of 8 rows.
+// `qcode` is the 16-bit code of q[tid] for tid < DH.  Three barriers; the first also publishes
+// whatever the caller wrote to LDS before the call.  Returns tau.
+template <class T, int DH>
+__device__ __forceinline__ float select_channels(const QueryLds& Q, uint16_t qcode, int r, int tid, int lane, int wave) {
+  if (tid < DH) {
+    Q.mag[tid] = ((uint32_t)(qcode & 0x7fffu) << 9) | (uint32_t)(511 - tid);
+    Q.qf[tid] = T::widen(qcode);
+  }
+  __syncthreads();
+  {
+    constexpr int SL = NT / DH, PER = DH / SL;
+    const int j = tid % DH, slice = tid / DH;
+    const uint32_t mine = Q.mag[j];
+    int partial = 0;
+#pragma unroll
+    for (int i4 = 0; i4 < PER; i4 += 4) {
+      const uint4 m = *reinterpret_cast<const uint4*>(Q.mag + slice * PER + i4);
+      partial += (m.x > mine) + (m.y > mine) + (m.z > mine) + (m.w > mine);
+    }
+    Q.rankp[slice * DH + j] = partial;
+  }
+  __syncthreads();
+  float tau;
+  {
+    constexpr int SL = NT / DH, NG = DH / kWave;
+    const int r8 = (r + 7) & ~7;
+    int before = 0;
+    float l1a = 0.0f, l1s = 0.0f;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const int jj = g * kWave + lane;
+      int rank = 0;
+#pragma unroll
+      for (int s = 0; s < SL; ++s) rank += Q.rankp[s * DH + jj];
+      const bool sel = rank < r;
+      const float qv = Q.qf[jj], aq = fabsf(qv);
+      const uint64_t bal = __ballot(sel);
+      if (g == wave && sel) {
+        const int p = before + __popcll(bal & ((1ull << lane) - 1ull));
+        Q.chan[p] = jj; Q.qs[p] = qv;
+        if (p == r - 1)
+          for (int pp = r; pp < r8; ++pp) { Q.chan[pp] = jj; Q.qs[pp] = 0.0f; }
+      }
+      before += __popcll(bal);
+      l1a += aq; l1s += sel ? aq : 0.0f;
+    }
+    const float l1_all = wave_sum(l1a), l1_sel = wave_sum(l1s);
+    tau = l1_all > 0.0f ? sqrtf((float)DH * l1_sel / l1_all) : sqrtf((float)DH);
+  }
+  __syncthreads();
+  return tau;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Step 1b: approximate logit numerators over the r selected rows of the S-contiguous key copy
+
+// Chunks (8 consecutive positions = 16 bytes of every channel row) chunk_begin + tid + i * NT belong to
+// thread tid.  The (chunk, batch-of-8-rows) pairs a thread owns form one flat sequence that runs through
+// a two-deep software pipeline: a batch of 8 loads is always in flight behind the one being accumulated,
+// also across chunk boundaries.  fp32 FMA in ascending channel order.  finish(c, acc) is called with the
+// 8 sums of chunk c.  No barrier.
+template <class T, class Finish>
+__device__ __forceinline__ void stream_channel_rows(const char* Kt_head, size_t row_bytes, const int* chan,
+                                                    const float* qs, int r, int chunk_begin, int chunk_end,
+                                                    int tid, Finish&& finish) {
+  const int n_batches = (r + 7) >> 3;
+  const int n_chunks = chunk_end - chunk_begin;
+  const int my_chunks = n_chunks > tid ? (n_chunks - tid + NT - 1) / NT : 0;
+  const int items = my_chunks * n_batches;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  int ic = 0, ib = 0, cc = 0, cb = 0;   // issue and consume cursors: (own chunk number, batch)
+  auto issue_next = [&](uint4 (&v)[8]) {
+    const uint32_t voff = (uint32_t)(chunk_begin + tid + ic * NT) * 16u;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const int ch = __builtin_amdgcn_readfirstlane(chan[ib * 8 + t]);   // uniform: scalar row base
+      v[t] = load16(Kt_head + (size_t)ch * row_bytes + voff);
+    }
+    if (++ib == n_batches) { ib = 0; ++ic; }
+  };
+  auto consume_next = [&](const uint4 (&v)[8]) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const float qv = qs[cb * 8 + t];
+      float f[8];
+      unpack8<T>(v[t], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = fmaf(f[e], qv, acc[e]);
+    }
+    if (++cb == n_batches) {
+      finish(chunk_begin + tid + cc * NT, acc);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+      cb = 0; ++cc;
+    }
+  };
+  uint4 va[8], vb[8];
+  if (items > 0) {
+    issue_next(va);
+    int i = 0;
+    for (; i + 2 < items; i += 2) {
+      issue_next(vb);
+      consume_next(va);
+      issue_next(va);
+      consume_next(vb);
+    }
+    if (i + 1 < items) {
+      issue_next(vb);
+      consume_next(va);
+      consume_next(vb);
+    } else {
+      consume_next(va);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Step 2a: the kq positions with the largest keys (ties to the lower position)
+
+struct SelectLds {
+  uint32_t* hist;   // [2][kRadixBins] double-buffered digit histograms (swizzled slots)
+  uint32_t* wcnt;   // [2][NW]
+  int* ctl;         // [8]
+  float* red;       // [2 * NW]
+};
+
+// Radix select with digits of 11, 11 and 10 bits from the top.  On entry hist[0] holds the counts of
+// the first digit of keys[0..S) and hist[1] is zero.  Pass p counts into hist[p & 1] while the other
+// buffer is cleared; one wave finds the threshold digit, everyone picks it up after a barrier; the loop
+// ends as soon as the remaining bin is taken whole.  On return the selected keys are those with
+// (key & pmask) > pval plus the first `need` keys (by position) with (key & pmask) == pval.
+__device__ __forceinline__ void radix_select(const uint32_t* keys, int S, int kq, const SelectLds& sl,
+                                             int tid, int lane, int wave, uint32_t& pmask, uint32_t& pval, int& need) {
+  const int n_chunks = (S + 7) >> 3;
+  pmask = 0u; pval = 0u; need = kq;
+  for (int pass = 0; pass < 3; ++pass) {
+    const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
+    const uint32_t dmask = pass == 2 ? 0x3ffu : 0x7ffu;
+    uint32_t* hist = sl.hist + (pass & 1) * kRadixBins;
+    if (pass > 0) {
+      uint32_t* other = sl.hist + ((pass + 1) & 1) * kRadixBins;   // free since the last barrier
+      for (int i = tid; i < kRadixBins; i += NT) other[i] = 0u;
+      for (int c = tid; c < n_chunks; c += NT) {
+        const uint4* src = reinterpret_cast<const uint4*>(keys + c * 8);
+        const uint4 lo = src[0], hi = src[1];
+        const uint32_t kx[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (c * 8 + e < S && (kx[e] & pmask) == pval) atomicAdd(&hist[hist_slot((kx[e] >> shift) & dmask)], 1u);
+      }
+      __syncthreads();
+    }
+    if (wave == 0) find_threshold_bin(hist, need, lane, sl.ctl);
+    __syncthreads();
+    pval |= (uint32_t)sl.ctl[0] << shift;
+    pmask |= dmask << shift;
+    need = sl.ctl[1];
+    const int in_bin = sl.ctl[2];
+    if (need == in_bin) break;   // every key matching the decided bits is taken: no ties to split
+  }
+}
+
+// Ordered compaction of the selected positions into list[0..kq) (ascending) and
+// alpha = (sum over the selected of exp((d - dmax)/tau)) / (sum over all): Step 3's weight.
+// `list` may be the key array itself: the list overwrites it from the front; a thread never writes
+// past the end of its own chunk and all reads of a sweep precede its writes (the scan's barrier).
+// Ends with a barrier that also publishes the list.  esc = log2(e) / tau.
+__device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t* list, int S, uint32_t pmask,
+                                                  uint32_t pval, int need, float dmax, float esc, int32_t* idx_out,
+                                                  int idx_stride, const SelectLds& sl, int tid, int lane, int wave) {
+  const int n_chunks = (S + 7) >> 3;
+  float zsum = 0.0f, asum = 0.0f;
+  uint32_t run_gt = 0, run_eq = 0;
+  int sweep = 0;
+  for (int c0 = 0; c0 < n_chunks; c0 += NT, ++sweep) {
+    const int c = c0 + tid;
+    uint32_t kx[8];
+    if (c < n_chunks) {
+      const uint4* src = reinterpret_cast<const uint4*>(keys + c * 8);
+      const uint4 lo = src[0], hi = src[1];
+      kx[0] = lo.x; kx[1] = lo.y; kx[2] = lo.z; kx[3] = lo.w;
+      kx[4] = hi.x; kx[5] = hi.y; kx[6] = hi.z; kx[7] = hi.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) kx[e] = 0u;
+    }
+    uint32_t n_gt = 0, n_eq = 0, gt_bits = 0, eq_bits = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const bool valid = (c * 8 + e) < S && c < n_chunks;
+      const uint32_t hi_bits = kx[e] & pmask;
+      const bool g = valid && hi_bits > pval, q = valid && hi_bits == pval;
+      gt_bits |= (uint32_t)g << e; eq_bits |= (uint32_t)q << e;
+      n_gt += g; n_eq += q;
+    }
+    uint32_t total;
+    const uint32_t ex = block_scan_excl(n_gt | (n_eq << 16), sl.wcnt + (sweep & 1) * NW, lane, wave, &total);
+    const uint32_t gt_before = run_gt + (ex & 0xffffu);
+    uint32_t eq_before = run_eq + (ex >> 16);
+    uint32_t o = gt_before + (eq_before < (uint32_t)need ? eq_before : (uint32_t)need);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const bool valid = (c * 8 + e) < S && c < n_chunks;
+      if (valid) {
+        const float w = exp2f((key_to_float(kx[e]) - dmax) * esc);
+        zsum += w;
+        bool take = (gt_bits >> e) & 1u;
+        if ((eq_bits >> e) & 1u) { take = eq_before < (uint32_t)need; ++eq_before; }
+        if (take) {
+          asum += w;
+          list[o] = (uint32_t)(c * 8 + e);
+          if (idx_out && (int)o < idx_stride) idx_out[o] = c * 8 + e;
+          ++o;
+        }
+      }
+    }
+    run_gt += total & 0xffffu;
+    run_eq += total >> 16;
+  }
+  zsum = wave_sum(zsum); asum = wave_sum(asum);
+  if (lane == 0) { sl.red[wave] = zsum; sl.red[NW + wave] = asum; }
+  __syncthreads();
+  float zt = 0.0f, at = 0.0f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) { zt += sl.red[w]; at += sl.red[NW + w]; }
+  return at / zt;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Step 2b: exact softmax attention over gathered rows (Eq. 6), online softmax in the exp2 domain
+
+template <int DH>
+struct RowGeometry {
+  static constexpr int LPR = DH / 8;          // lanes per row (16 bytes each)
+  static constexpr int RPW = kWave / LPR;     // rows per wave per load
+  static constexpr int RPI = NW * RPW;        // rows per workgroup per load
+  static constexpr int UNR = 4;
+  static constexpr int GROUP = RPI * UNR;     // rows the workgroup covers per group of loads
+};
+
+// Rows list[n_begin..n_end) of K and V (K_head / V_head already offset by the lane's 16-byte column
+// slice `sub`).  LPR lanes share a row, K and V rows are issued together, groups of UNR loads run
+// through a two-deep software pipeline.  q8 = the lane's 8 query components times log2(e)/sqrt(d_h).
+// If new_index >= 0, list entry new_index is the row being appended by this step and is taken from
+// the codes knew / vnew instead of the cache.  Accumulates into (m_run, l_run, acc).  No barrier.
+template <class T, int DH, bool APPEND>
+__device__ __forceinline__ void attend_rows(const char* K_head, const char* V_head, const int* list, int n_begin,
+                                            int n_end, const float (&q8)[8], int new_index, const uint16_t* knew,
+                                            const uint16_t* vnew, int lane, int wave, float& m_run, float& l_run,
+                                            float (&acc)[8]) {
+  using G = RowGeometry<DH>;
+  const int sub = lane % G::LPR, slot = wave * G::RPW + lane / G::LPR;
+  const int n_groups = (n_end - n_begin + G::GROUP - 1) / G::GROUP;
+  auto issue = [&](uint4 (&kr)[G::UNR], uint4 (&vr)[G::UNR], int g) {
+#pragma unroll
+    for (int t = 0; t < G::UNR; ++t) {
+      const int n = n_begin + g * G::GROUP + t * G::RPI + slot;
+      const uint32_t off = (uint32_t)list[n < n_end ? n : n_end - 1] * (uint32_t)(DH * 2);   // < S_max * 512 bytes
+      kr[t] = load16(K_head + off);
+      vr[t] = load16(V_head + off);
+    }
+  };
+  auto consume = [&](const uint4 (&kr)[G::UNR], const uint4 (&vr)[G::UNR], int g) {
+#pragma unroll
+    for (int t = 0; t < G::UNR; ++t) {
+      const int n = n_begin + g * G::GROUP + t * G::RPI + slot;
+      float f[8];
+      const bool from_inputs = APPEND && n == new_index;
+      const uint4 kt = from_inputs ? *reinterpret_cast<const uint4*>(knew + sub * 8) : kr[t];
+      const uint4 vt = from_inputs ? *reinterpret_cast<const uint4*>(vnew + sub * 8) : vr[t];
+      unpack8<T>(kt, f);
+      float dot = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dot = fmaf(f[e], q8[e], dot);
+      dot = lanes_sum<G::LPR>(dot);
+      if (n < n_end) {
+        const float m_new = fmaxf(m_run, dot);
+        const float sc = exp2f(m_run - m_new), pr = exp2f(dot - m_new);
+        unpack8<T>(vt, f);
+        l_run = l_run * sc + pr;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = acc[e] * sc + pr * f[e];
+        m_run = m_new;
+      }
+    }
+  };
+  if (n_groups > 0) {
+    uint4 ka[G::UNR], va[G::UNR], kb[G::UNR], vb[G::UNR];
+    issue(ka, va, 0);
+    int g = 0;
+    for (; g + 2 < n_groups; g += 2) {
+      issue(kb, vb, g + 1);
+      consume(ka, va, g);
+      issue(ka, va, g + 2);
+      consume(kb, vb, g + 1);
+    }
+    if (g + 1 < n_groups) {
+      issue(kb, vb, g + 1);
+      consume(ka, va, g);
+      consume(kb, vb, g + 1);
+    } else {
+      consume(ka, va, g);
+    }
+  }
+}
+
+// Merge the lane groups of a wave (butterfly over the group index) and store the wave's partial
+// (acc[DH], m, l) to part[wave][DH + 2].  The caller puts a barrier after it.
+template <int DH>
+__device__ __forceinline__ void store_wave_partial(float m_run, float l_run, float (&acc)[8], float* part, int lane, int wave) {
+  using G = RowGeometry<DH>;
+#pragma unroll
+  for (int o = G::LPR; o < kWave; o <<= 1) {
+    const float m_o = __shfl_xor(m_run, o), l_o = __shfl_xor(l_run, o);
+    const float m_new = fmaxf(m_run, m_o);
+    const float s1 = weight_exp2(m_run, m_new), s2 = weight_exp2(m_o, m_new);
+    l_run = l_run * s1 + l_o * s2;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = acc[e] * s1 + __shfl_xor(acc[e], o) * s2;
+    m_run = m_new;
+  }
+  float* mine = part + wave * (DH + 2);
+  if (lane < G::LPR) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) mine[lane * 8 + e] = acc[e];
+    if (lane == 0) { mine[DH] = m_run; mine[DH + 1] = l_run; }
+  }
+}
+
+// Channel c of the merge of n_parts partials laid out [n_parts][DH + 2]: running max, denominator and
+// un-normalised numerator (each partial's numerator and denominator are relative to its own max).
+template <int DH>
+__device__ __forceinline__ void combine_partials(const float* parts, int n_parts, int c, float& m_all, float& l_all, float& y) {
+  m_all = -INFINITY;
+  for (int w = 0; w < n_parts; ++w) m_all = fmaxf(m_all, parts[w * (DH + 2) + DH]);
+  l_all = 0.0f; y = 0.0f;
+  for (int w = 0; w < n_parts; ++w) {
+    const float s = weight_exp2(parts[w * (DH + 2) + DH], m_all);
+    l_all += parts[w * (DH + 2) + DH + 1] * s;
+    y += parts[w * (DH + 2) + c] * s;
+  }
+}
+
+}  // namespace sparq
