@@ -76,11 +76,13 @@ typedef struct {
   int32_t* seq_lens; /* device */
 } sparq_cache;
 
-/* Bytes of device workspace the calls below need for this shape (>= 256).  The first word
- * of the workspace is the error word; sparq_workspace_init zeroes it. */
+/* Bytes of device workspace the calls below need for this shape (>= 64 KiB).  The first 64 KiB
+ * are a control block (word 0 is the error word, then arrival counters of the split-sequence
+ * kernels) that sparq_workspace_init zeroes; the rest is scratch for dense_decode and for
+ * sparq_decode on batches with few heads and long caches.  One workspace serves one stream. */
 int sparq_workspace_bytes(const sparq_shape* shape, size_t* out_bytes);
 
-/* Enqueue a clear of the workspace header.  Call once after allocating the workspace. */
+/* Enqueue a clear of the control block.  Call once after allocating the workspace. */
 int sparq_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*

@@ -47,10 +47,49 @@ void dense_plan(const sparq_shape* s, int* n_split, int* rows_per_split) {
   *n_split = (s->S_max + rows - 1) / rows;
 }
 
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// The split-sequence plan serves batches with few (sequence, head) units and long caches: the
+// positions of every unit are divided over n_split workgroups (about 512 workgroups in all, slices
+// of at least 1024 positions).  Everything else runs one workgroup per unit.
+bool split_plan(const sparq_shape* s, int* n_split) {
+  const int64_t units = (int64_t)s->B * s->H;
+  if (units > kSplitMaxUnits || s->S_max < 8192) return false;
+  int64_t n = 512 / units;
+  if (n > kMaxSplit) n = kMaxSplit;
+  if (n > s->S_max / 1024) n = s->S_max / 1024;
+  *n_split = (int)n;
+  return n >= 2;
+}
+
+// workspace: [0, kControlBytes) control block (error word, arrival counters), then either the
+// dense_decode partials or the arrays of the split-sequence plan (they are never live together)
+struct SplitLayout { size_t tmax, tau, alpha, keys, list, part, end; };
+
+SplitLayout split_layout(const sparq_shape* s, int n_split) {
+  const size_t units = (size_t)s->B * s->H;
+  SplitLayout l;
+  size_t off = kControlBytes;
+  l.tmax = off; off = align256(off + units * n_split * sizeof(float));
+  l.tau = off; off = align256(off + units * sizeof(float));
+  l.alpha = off; off = align256(off + units * sizeof(float));
+  l.keys = off; off = align256(off + units * s->S_max * sizeof(uint32_t));
+  l.list = off; off = align256(off + units * s->S_max * sizeof(int32_t));
+  l.part = off; off = align256(off + units * n_split * (s->d_h + 2) * sizeof(float));
+  l.end = off;
+  return l;
+}
+
 size_t workspace_need(const sparq_shape* s) {
   int n_split, rows;
   dense_plan(s, &n_split, &rows);
-  return (size_t)kWorkspaceHeader + (size_t)s->B * s->H * n_split * (s->d_h + 2) * sizeof(float);
+  size_t need = (size_t)kControlBytes + (size_t)s->B * s->H * n_split * (s->d_h + 2) * sizeof(float);
+  int ns;
+  if (split_plan(s, &ns)) {
+    const size_t e = split_layout(s, ns).end;
+    if (e > need) need = e;
+  }
+  return need;
 }
 
 int check_workspace(const sparq_shape* s, const void* ws, size_t bytes) {
@@ -69,6 +108,43 @@ int max_lds_bytes() {
   return cached;
 }
 
+// enqueue one decode over `a` with the plan the shape calls for
+hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* workspace, hipStream_t s) {
+  int n_split;
+  if (!split_plan(shape, &n_split)) return launch_decode(a, shape->dtype, s);
+  const SplitLayout l = split_layout(shape, n_split);
+  char* w = static_cast<char*>(workspace);
+  SplitArgs sa;
+  sa.d = a;
+  sa.n_split = n_split;
+  sa.tmax_ws = reinterpret_cast<float*>(w + l.tmax);
+  sa.tau_ws = reinterpret_cast<float*>(w + l.tau);
+  sa.alpha_ws = reinterpret_cast<float*>(w + l.alpha);
+  sa.keys_ws = reinterpret_cast<uint32_t*>(w + l.keys);
+  sa.list_ws = reinterpret_cast<int32_t*>(w + l.list);
+  sa.part_ws = reinterpret_cast<float*>(w + l.part);
+  if (a.k_new) {
+    // the one-launch step has no split form: append into the *_next state, then decode from it
+    AppendArgs ap;
+    ap.K = a.K; ap.Kt = a.Kt; ap.V = a.V; ap.v_mean = const_cast<float*>(a.v_mean); ap.seq_lens = const_cast<int32_t*>(a.seq_lens);
+    ap.v_mean_out = a.v_mean_next; ap.seq_lens_out = a.seq_lens_next;
+    ap.k_new = a.k_new; ap.v_new = a.v_new; ap.n_new_per_seq = nullptr; ap.err = a.err;
+    ap.B = a.B; ap.H_kv = a.H_kv; ap.S_max = a.S_max; ap.d_h = a.d_h; ap.n_new = 1;
+    hipError_t e = launch_append(ap, shape->dtype, s);
+    if (e != hipSuccess) return e;
+    sa.d.v_mean = a.v_mean_next; sa.d.seq_lens = a.seq_lens_next;
+    sa.d.k_new = nullptr; sa.d.v_new = nullptr; sa.d.v_mean_next = nullptr; sa.d.seq_lens_next = nullptr;
+  }
+  return launch_decode_split(sa, shape->dtype, s);
+}
+
+// the one-workgroup-per-unit kernel keeps one 4-byte key per cached position in LDS
+bool decode_supported(const sparq_shape* shape) {
+  int n_split;
+  if (split_plan(shape, &n_split)) return split_select_lds_bytes(shape->S_max) <= (size_t)max_lds_bytes();
+  return decode_lds_bytes(shape->S_max, shape->d_h) <= (size_t)max_lds_bytes();
+}
+
 }  // namespace
 
 extern "C" {
@@ -82,8 +158,8 @@ int sparq_workspace_bytes(const sparq_shape* shape, size_t* out_bytes) {
 }
 
 int sparq_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!workspace || !aligned16(workspace) || workspace_bytes < (size_t)kWorkspaceHeader) return SPARQ_EWORKSPACE;
-  return launch_clear_header(workspace, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
+  if (!workspace || !aligned16(workspace) || workspace_bytes < (size_t)kControlBytes) return SPARQ_EWORKSPACE;
+  return launch_clear(workspace, kControlBytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
 int sparq_kv_append(const sparq_shape* shape, const sparq_cache* cache, const void* k_new,
@@ -97,6 +173,7 @@ int sparq_kv_append(const sparq_shape* shape, const sparq_cache* cache, const vo
   if (rc != SPARQ_OK) return rc;
   AppendArgs a;
   a.K = cache->K; a.Kt = cache->Kt; a.V = cache->V; a.v_mean = cache->v_mean; a.seq_lens = cache->seq_lens;
+  a.v_mean_out = cache->v_mean; a.seq_lens_out = cache->seq_lens;
   a.k_new = k_new; a.v_new = v_new; a.n_new_per_seq = n_new_per_seq; a.err = static_cast<int32_t*>(workspace);
   a.B = shape->B; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h; a.n_new = n_new;
   return launch_append(a, shape->dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
@@ -114,8 +191,7 @@ int sparq_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
   rc = check_workspace(shape, workspace, workspace_bytes);
   if (rc != SPARQ_OK) return rc;
   if (shape->flags & SPARQ_FLAG_GQA_SHARED) return SPARQ_EUNSUPPORTED;
-  // the fused kernel keeps one 4-byte key per cached position in LDS
-  if (decode_lds_bytes(shape->S_max, shape->d_h) > (size_t)max_lds_bytes()) return SPARQ_EUNSUPPORTED;
+  if (!decode_supported(shape)) return SPARQ_EUNSUPPORTED;
   DecodeArgs a;
   a.K = cache->K; a.Kt = cache->Kt; a.V = cache->V; a.v_mean = cache->v_mean; a.seq_lens = cache->seq_lens;
   a.q = q; a.k_per_seq = k_per_seq; a.out = out; a.alpha_out = alpha_out; a.idx_out = idx_out;
@@ -123,7 +199,7 @@ int sparq_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
   a.chan_out = chan_out; a.err = static_cast<int32_t*>(workspace);
   a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h;
   a.r = shape->r; a.k = shape->k; a.idx_stride = idx_out ? idx_stride : 0; a.flags = shape->flags;
-  return launch_decode(a, shape->dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
+  return enqueue_decode(shape, a, workspace, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
 int sparq_decode_step(const sparq_shape* shape, const sparq_cache* cache, const void* k_new,
@@ -142,7 +218,7 @@ int sparq_decode_step(const sparq_shape* shape, const sparq_cache* cache, const 
   rc = check_workspace(shape, workspace, workspace_bytes);
   if (rc != SPARQ_OK) return rc;
   if (shape->flags & SPARQ_FLAG_GQA_SHARED) return SPARQ_EUNSUPPORTED;
-  if (decode_lds_bytes(shape->S_max, shape->d_h) > (size_t)max_lds_bytes()) return SPARQ_EUNSUPPORTED;
+  if (!decode_supported(shape)) return SPARQ_EUNSUPPORTED;
   DecodeArgs a;
   a.K = cache->K; a.Kt = cache->Kt; a.V = cache->V; a.v_mean = cache->v_mean; a.seq_lens = cache->seq_lens;
   a.q = q; a.k_per_seq = k_per_seq; a.out = out; a.alpha_out = alpha_out; a.idx_out = idx_out;
@@ -150,7 +226,7 @@ int sparq_decode_step(const sparq_shape* shape, const sparq_cache* cache, const 
   a.chan_out = chan_out; a.err = static_cast<int32_t*>(workspace);
   a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h;
   a.r = shape->r; a.k = shape->k; a.idx_stride = idx_out ? idx_stride : 0; a.flags = shape->flags;
-  return launch_decode(a, shape->dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
+  return enqueue_decode(shape, a, workspace, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
 int dense_decode(const sparq_shape* shape, const sparq_cache* cache, const void* q, void* out,
@@ -163,7 +239,7 @@ int dense_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
   if (rc != SPARQ_OK) return rc;
   DenseArgs a;
   a.K = cache->K; a.V = cache->V; a.seq_lens = cache->seq_lens; a.q = q; a.out = out;
-  a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kWorkspaceHeader);
+  a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kControlBytes);
   a.err = static_cast<int32_t*>(workspace);
   a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h;
   dense_plan(shape, &a.n_split, &a.rows_per_split);
@@ -174,7 +250,7 @@ int sparq_async_error(void* workspace, int32_t* host_flag, void* hip_stream) {
   if (!workspace || !host_flag) return SPARQ_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (hipMemcpyAsync(host_flag, workspace, sizeof(int32_t), hipMemcpyDeviceToHost, s) != hipSuccess) return SPARQ_ELAUNCH;
-  if (launch_clear_header(workspace, s) != hipSuccess) return SPARQ_ELAUNCH;
+  if (launch_clear(workspace, kWorkspaceHeader, s) != hipSuccess) return SPARQ_ELAUNCH;
   return hipStreamSynchronize(s) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 

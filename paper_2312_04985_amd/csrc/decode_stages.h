@@ -14,24 +14,6 @@ constexpr int NW = NT / kWave;   // waves per workgroup
 // ------------------------------------------------------------------------------------------------
 // small workgroup primitives
 
-// Exclusive prefix sum of v over the workgroup in thread order; *total gets the sum.
-// One barrier; callers alternate `wsum` between two NW-word buffers on consecutive calls.
-__device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wsum, int lane, int wave,
-                                                    uint32_t* total) {
-  const uint32_t incl = wave_scan_incl(v);
-  if (lane == kWave - 1) wsum[wave] = incl;
-  __syncthreads();
-  uint32_t before = 0, all = 0;
-#pragma unroll
-  for (int w = 0; w < NW; ++w) {
-    const uint32_t t = wsum[w];
-    if (w < wave) before += t;
-    all += t;
-  }
-  *total = all;
-  return before + incl - v;
-}
-
 // Histogram bins are stored swizzled so that the 32 consecutive digits a lane sums in
 // find_threshold_bin sit in 32 different rows of 64 words: lane-consecutive, conflict-free reads.
 __device__ __forceinline__ uint32_t hist_slot(uint32_t digit) { return ((digit & 31u) << 6) | (digit >> 5); }
@@ -196,7 +178,7 @@ __device__ __forceinline__ void stream_channel_rows(const char* Kt_head, size_t 
 
 struct SelectLds {
   uint32_t* hist;   // [2][kRadixBins] double-buffered digit histograms (swizzled slots)
-  uint32_t* wcnt;   // [2][NW]
+  uint32_t* wcnt;   // [2][NW] wave totals of the compaction scan, double-buffered
   int* ctl;         // [8]
   float* red;       // [2 * NW]
 };
@@ -237,10 +219,31 @@ __device__ __forceinline__ void radix_select(const uint32_t* keys, int S, int kq
   }
 }
 
+// Exclusive prefix sum of v over the workgroup in thread order; *total gets the sum.
+// One barrier; callers alternate `wsum` between two NW-word buffers on consecutive calls.
+__device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wsum, int lane, int wave,
+                                                    uint32_t* total) {
+  const uint32_t incl = wave_scan_incl(v);
+  if (lane == kWave - 1) wsum[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    const uint32_t t = wsum[w];
+    if (w < wave) before += t;
+    all += t;
+  }
+  *total = all;
+  return before + incl - v;
+}
+
 // Ordered compaction of the selected positions into list[0..kq) (ascending) and
 // alpha = (sum over the selected of exp((d - dmax)/tau)) / (sum over all): Step 3's weight.
-// `list` may be the key array itself: the list overwrites it from the front; a thread never writes
-// past the end of its own chunk and all reads of a sweep precede its writes (the scan's barrier).
+// One sweep covers NT chunks (thread tid owns chunk base + tid), with one workgroup scan of the
+// packed (above-threshold, equal-to-threshold) counts per sweep.  (Wider sweeps with fewer barriers
+// were measured and are not faster: the sweep is bound by its arithmetic, not by the barrier.)
+// `list` may be the key array itself: the list overwrites it from the front; a write never lands
+// beyond the position it records and all reads of a sweep precede its writes (the scan's barrier).
 // Ends with a barrier that also publishes the list.  esc = log2(e) / tau.
 __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t* list, int S, uint32_t pmask,
                                                   uint32_t pval, int need, float dmax, float esc, int32_t* idx_out,
@@ -318,15 +321,13 @@ struct RowGeometry {
 // Rows list[n_begin..n_end) of K and V (K_head / V_head already offset by the lane's 16-byte column
 // slice `sub`).  LPR lanes share a row, K and V rows are issued together, groups of UNR loads run
 // through a two-deep software pipeline.  q8 = the lane's 8 query components times log2(e)/sqrt(d_h).
-// If new_index >= 0, list entry new_index is the row being appended by this step and is taken from
-// the codes knew / vnew instead of the cache.  Accumulates into (m_run, l_run, acc).  No barrier.
-template <class T, int DH, bool APPEND>
+// Accumulates into (m_run, l_run, acc).  No barrier.
+template <class T, int DH>
 __device__ __forceinline__ void attend_rows(const char* K_head, const char* V_head, const int* list, int n_begin,
-                                            int n_end, const float (&q8)[8], int new_index, const uint16_t* knew,
-                                            const uint16_t* vnew, int lane, int wave, float& m_run, float& l_run,
-                                            float (&acc)[8]) {
+                                            int n_end, const float (&q8)[8], int lane, int wave, float& m_run,
+                                            float& l_run, float (&acc)[8]) {
   using G = RowGeometry<DH>;
-  const int sub = lane % G::LPR, slot = wave * G::RPW + lane / G::LPR;
+  const int slot = wave * G::RPW + lane / G::LPR;
   const int n_groups = (n_end - n_begin + G::GROUP - 1) / G::GROUP;
   auto issue = [&](uint4 (&kr)[G::UNR], uint4 (&vr)[G::UNR], int g) {
 #pragma unroll
@@ -342,10 +343,7 @@ __device__ __forceinline__ void attend_rows(const char* K_head, const char* V_he
     for (int t = 0; t < G::UNR; ++t) {
       const int n = n_begin + g * G::GROUP + t * G::RPI + slot;
       float f[8];
-      const bool from_inputs = APPEND && n == new_index;
-      const uint4 kt = from_inputs ? *reinterpret_cast<const uint4*>(knew + sub * 8) : kr[t];
-      const uint4 vt = from_inputs ? *reinterpret_cast<const uint4*>(vnew + sub * 8) : vr[t];
-      unpack8<T>(kt, f);
+      unpack8<T>(kr[t], f);
       float dot = 0.0f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) dot = fmaf(f[e], q8[e], dot);
@@ -353,7 +351,7 @@ __device__ __forceinline__ void attend_rows(const char* K_head, const char* V_he
       if (n < n_end) {
         const float m_new = fmaxf(m_run, dot);
         const float sc = exp2f(m_run - m_new), pr = exp2f(dot - m_new);
-        unpack8<T>(vt, f);
+        unpack8<T>(vr[t], f);
         l_run = l_run * sc + pr;
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] = acc[e] * sc + pr * f[e];
@@ -378,6 +376,30 @@ __device__ __forceinline__ void attend_rows(const char* K_head, const char* V_he
     } else {
       consume(ka, va, g);
     }
+  }
+}
+
+// One more row, given as 16-bit codes in LDS (the row a decode step appends), folded into the state of
+// the lane group with slot 0.  Executed by all lanes; no barrier.
+template <class T, int DH>
+__device__ __forceinline__ void attend_row_from_codes(const uint16_t* krow, const uint16_t* vrow, const float (&q8)[8],
+                                                      int lane, int wave, float& m_run, float& l_run, float (&acc)[8]) {
+  using G = RowGeometry<DH>;
+  const int sub = lane % G::LPR;
+  float f[8];
+  unpack8<T>(*reinterpret_cast<const uint4*>(krow + sub * 8), f);
+  float dot = 0.0f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) dot = fmaf(f[e], q8[e], dot);
+  dot = lanes_sum<G::LPR>(dot);
+  if (wave == 0 && lane < G::LPR) {
+    const float m_new = fmaxf(m_run, dot);
+    const float sc = exp2f(m_run - m_new), pr = exp2f(dot - m_new);
+    unpack8<T>(*reinterpret_cast<const uint4*>(vrow + sub * 8), f);
+    l_run = l_run * sc + pr;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = acc[e] * sc + pr * f[e];
+    m_run = m_new;
   }
 }
 

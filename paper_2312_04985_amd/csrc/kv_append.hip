@@ -16,9 +16,17 @@ __global__ __launch_bounds__(512) void append_one_row(const AppendArgs a) {
   const int S = a.seq_lens[b];
   int n = a.n_new_per_seq ? a.n_new_per_seq[b] : 1;
   n = n < 0 ? 0 : (n > 1 ? 1 : n);
-  if (n == 0) return;
-  if (S < 0 || S + 1 > a.S_max) {
-    if (tid == 0) atomicOr(a.err, 1);
+  const bool in_place = a.v_mean_out == a.v_mean;
+  const bool full = S < 0 || S + 1 > a.S_max;
+  if (n == 0 || full) {      // nothing appended: the state is carried over unchanged
+    if (full && n != 0 && tid == 0) atomicOr(a.err, 1);
+    if (!in_place) {
+      for (int i = tid; i < a.H_kv * a.d_h; i += 512) {
+        const size_t e = (size_t)b * a.H_kv * a.d_h + i;
+        a.v_mean_out[e] = a.v_mean[e];
+      }
+      if (tid == 0) a.seq_lens_out[b] = S;
+    }
     return;
   }
   const int cpr = a.d_h / 8;                  // 16-byte chunks per row
@@ -40,17 +48,18 @@ __global__ __launch_bounds__(512) void append_one_row(const AppendArgs a) {
     for (int e = 0; e < 8; ++e)
       Ktcol[(size_t)e * a.S_max] = (uint16_t)((e & 1) ? (kw[e >> 1] >> 16) : (kw[e >> 1] & 0xffffu));
     // running mean: v_mean += (v - v_mean) / (S + 1)
-    float* vm = a.v_mean + head * a.d_h + j0;
-    float4 m0 = *reinterpret_cast<float4*>(vm), m1 = *reinterpret_cast<float4*>(vm + 4);
+    const float* vm = a.v_mean + head * a.d_h + j0;
+    float* vo = a.v_mean_out + head * a.d_h + j0;
+    float4 m0 = *reinterpret_cast<const float4*>(vm), m1 = *reinterpret_cast<const float4*>(vm + 4);
     float f[8];
     unpack8<T>(vc, f);
     m0.x += (f[0] - m0.x) * inv; m0.y += (f[1] - m0.y) * inv; m0.z += (f[2] - m0.z) * inv; m0.w += (f[3] - m0.w) * inv;
     m1.x += (f[4] - m1.x) * inv; m1.y += (f[5] - m1.y) * inv; m1.z += (f[6] - m1.z) * inv; m1.w += (f[7] - m1.w) * inv;
-    *reinterpret_cast<float4*>(vm) = m0;
-    *reinterpret_cast<float4*>(vm + 4) = m1;
+    *reinterpret_cast<float4*>(vo) = m0;
+    *reinterpret_cast<float4*>(vo + 4) = m1;
   }
   __syncthreads();
-  if (tid == 0) a.seq_lens[b] = S + 1;
+  if (tid == 0) a.seq_lens_out[b] = S + 1;
 }
 
 // ---- many rows per sequence (prefill / cache construction) ----
@@ -156,8 +165,8 @@ __global__ __launch_bounds__(256) void read_probe(const uint4* src, size_t n16, 
   sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = acc;
 }
 
-__global__ void clear_header(int32_t* w) {
-  if (threadIdx.x < kWorkspaceHeader / 4) w[threadIdx.x] = 0;
+__global__ void clear_words(int32_t* w, int n) {
+  for (int i = threadIdx.x; i < n; i += blockDim.x) w[i] = 0;
 }
 
 template <class T>
@@ -198,8 +207,8 @@ hipError_t launch_read_probe(const void* src, size_t n_bytes, void* sink, hipStr
   return hipGetLastError();
 }
 
-hipError_t launch_clear_header(void* workspace, hipStream_t s) {
-  hipLaunchKernelGGL(clear_header, dim3(1), dim3(64), 0, s, reinterpret_cast<int32_t*>(workspace));
+hipError_t launch_clear(void* workspace, int n_bytes, hipStream_t s) {
+  hipLaunchKernelGGL(clear_words, dim3(1), dim3(256), 0, s, reinterpret_cast<int32_t*>(workspace), n_bytes / 4);
   return hipGetLastError();
 }
 

@@ -9,6 +9,9 @@ namespace sparq {
 constexpr int kDecodeThreads = 512;     // threads per workgroup of the fused decode kernel
 constexpr int kRadixBins = 2048;        // 11-bit digits: passes of 11, 11 and 10 bits
 constexpr int kWorkspaceHeader = 256;   // bytes; word 0 is the error word
+constexpr int kControlBytes = 65536;    // control block at the start of the workspace, zeroed by sparq_workspace_init
+constexpr int kMaxSplit = 16;           // most workgroups one (sequence, head) is split over
+constexpr int kSplitMaxUnits = 128;     // the split-sequence plan serves at most this many (sequence, head) units
 constexpr int kProbeBlocks = 256 * 8;   // workgroups (of 256 threads) of the bandwidth probes
 
 struct DecodeArgs {
@@ -24,6 +27,7 @@ struct DecodeArgs {
 
 struct AppendArgs {
   void* K; void* Kt; void* V; float* v_mean; int32_t* seq_lens;
+  float* v_mean_out; int32_t* seq_lens_out;   // where the new means / lengths go (== v_mean / seq_lens: in place)
   const void* k_new; const void* v_new; const int32_t* n_new_per_seq; int32_t* err;
   int32_t B, H_kv, S_max, d_h, n_new;
 };
@@ -35,14 +39,28 @@ struct DenseArgs {
   int32_t B, H, H_kv, S_max, d_h, n_split, rows_per_split;
 };
 
+// split-sequence plan (few heads, long sequences): workspace arrays and the split count
+struct SplitArgs {
+  DecodeArgs d;
+  int32_t n_split;       // workgroups per (sequence, head) in both launches
+  float* tmax_ws;        // [B * H][n_split] largest logit numerator of each slice
+  float* tau_ws;         // [B * H]
+  float* alpha_ws;       // [B * H]
+  uint32_t* keys_ws;     // [B * H][S_max] integer keys of the approximate logits
+  int32_t* list_ws;      // [B * H][S_max] selected positions, ascending
+  float* part_ws;        // [B * H][n_split][d_h + 2] attention partials
+};
+
 // LDS bytes the fused decode kernel needs for a cache of S_max rows and head dimension d_h
 size_t decode_lds_bytes(int S_max, int d_h);
+size_t split_select_lds_bytes(int S_max);
 
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s);
+hipError_t launch_decode_split(const SplitArgs& a, int dtype, hipStream_t s);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t s);
 hipError_t launch_dense(const DenseArgs& a, int dtype, hipStream_t s);
 hipError_t launch_copy_probe(void* dst, const void* src, size_t n_bytes, hipStream_t s);
 hipError_t launch_read_probe(const void* src, size_t n_bytes, void* sink, hipStream_t s);
-hipError_t launch_clear_header(void* workspace, hipStream_t s);
+hipError_t launch_clear(void* workspace, int n_bytes, hipStream_t s);
 
 }  // namespace sparq

@@ -161,11 +161,13 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   float q8[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) q8[e] = L.qry.qf[sub * 8 + e] * qscale;
-  // positions are ascending, so the appended row (position S - 1) can only be the last entry
-  const int new_index = (APPEND && appended && list[kq - 1] == S - 1) ? kq - 1 : -1;
+  // positions are ascending, so the appended row (position S - 1) can only be the last entry; it is
+  // not read back from the cache but taken from the inputs
+  const bool new_selected = APPEND && appended && list[kq - 1] == S - 1;
   float m_run = -INFINITY, l_run = 0.0f;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  attend_rows<T, DH, APPEND>(K_head, V_head, list, 0, kq, q8, new_index, L.knew, L.vnew, lane, wave, m_run, l_run, acc);
+  attend_rows<T, DH>(K_head, V_head, list, 0, new_selected ? kq - 1 : kq, q8, lane, wave, m_run, l_run, acc);
+  if (APPEND && new_selected) attend_row_from_codes<T, DH>(L.knew, L.vnew, q8, lane, wave, m_run, l_run, acc);
   store_wave_partial<DH>(m_run, l_run, acc, L.part, lane, wave);
   __syncthreads();
   if (tid < DH) {

@@ -199,6 +199,7 @@ def test_unsupported_requests_are_refused():
     ("gqa_bf16", dict(B=2, H=8, H_kv=2, d_h=128, S=4100, r=32, k=512, dtype="bf16")),
     ("d256", dict(B=2, H=2, H_kv=2, d_h=256, S=1500, r=64, k=200, dtype="bf16")),
     ("d64_k_ge_s", dict(B=2, H=4, H_kv=2, d_h=64, S=40, r=8, k=64, dtype="f16")),
+    ("split_plan", dict(B=1, H=4, H_kv=2, d_h=128, S=9000, r=16, k=300, dtype="f16")),
 ])
 def test_decode_step_equals_append_then_decode(name, kw):
     """sparq_decode_step must leave exactly the state, and return exactly the outputs, of
@@ -255,3 +256,28 @@ def test_decode_step_on_a_full_sequence():
     assert b.cache.seq_lens.cpu().tolist() == [64, 31]
     assert torch.equal(out[0].view(torch.int16), ref[0].view(torch.int16)) and torch.equal(b.cache.v_mean[0], vm0[0])
     assert torch.equal(b.cache.K[1, :, 30], kn[1, :, 0]) and torch.equal(b.cache.Kt[1, :, :, 30], kn[1, :, 0])
+
+
+# ------------------------------------------------------------------ split-sequence plan (few heads, long cache)
+
+def test_split_plan_ragged_short_and_empty_sequences():
+    """S_max >= 8192 with few heads selects the split-sequence kernels; sequences much shorter than the
+    slices (empty slices), k >= S, an empty sequence and every d_h go through them too."""
+    for d_h, dtype, r in ((128, "f16", 16), (256, "bf16", 64), (64, "f16", 8)):
+        w = W.Workload("split_ragged", 4, 4, 2, d_h, 9000, r, 200, dtype, seed=40 + d_h)
+        seq = torch.tensor([9000, 37, 0, 1500], dtype=torch.int32)
+        b = Hn.build_cache(w, seq_lens=seq, S_max=9024, v_offset=True)
+        q = W.draw_queries(w, b.K_src, seq, n=2, q_scale=0.02)
+        for i in range(2):
+            c = b.cache
+            out, alpha, idx, chan = c.decode(q[i], aux=True)
+            torch.cuda.synchronize()
+            assert c.error_flags() == B.SPARQ_ERR_EMPTY_SEQ
+            assert (out[2] == 0).all() and (idx[2] == -1).all() and (alpha[2] == 0).all()
+        # the non-empty sequences against the oracle
+        keep = [0, 1, 3]
+        w3 = W.scaled(w, B=3)
+        sub = Hn.Built(w3, DecodeCache(3, w.H, w.H_kv, 9024, d_h, r, 200, w.torch_dtype), b.K_src[keep].contiguous(),
+                       b.V_src[keep].contiguous(), seq[keep], None)
+        sub.cache.append(sub.K_src, sub.V_src, seq[keep].cuda())
+        say(Hn.compare_decode(sub, q[0][keep].contiguous()))
