@@ -83,7 +83,8 @@ def main():
     K_src, V_src = W.draw_kv(w, dev, n_rows=int(seq0.max()))
     caches = []
     for _ in range(copies):
-        c = DecodeCache(w.B, w.H, w.H_kv, S_max, w.d_h, w.r, w.k, w.torch_dtype, device=dev)
+        c = DecodeCache(w.B, w.H, w.H_kv, S_max, w.d_h, w.r, w.k, w.torch_dtype, device=dev,
+                        flags=B.SPARQ_FLAG_RAGGED_BATCH if w.ragged else 0)
         c.append(K_src, V_src, (seq0 - 1).to(dev))
         caches.append(c)
     torch.cuda.synchronize()

@@ -49,7 +49,10 @@ enum {
   /* one channel set and one position set per KV head from group sums (Section 4,
    * "Grouped query attention").  Not built yet: returns SPARQ_EUNSUPPORTED.  The default
    * treats every query head independently over its shared KV head. */
-  SPARQ_FLAG_GQA_SHARED = 1u << 1
+  SPARQ_FLAG_GQA_SHARED = 1u << 1,
+  /* scheduling hint, no effect on results: the sequence lengths of the batch differ widely;
+   * sparq_decode / sparq_decode_step then start the longest sequences first */
+  SPARQ_FLAG_RAGGED_BATCH = 1u << 2
 };
 
 /* bits of the device-side error word (sparq_async_error) */

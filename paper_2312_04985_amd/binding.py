@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libsparq.so")
 
 SPARQ_F16, SPARQ_BF16 = 0, 1
-SPARQ_FLAG_NO_REALLOC, SPARQ_FLAG_GQA_SHARED = 1, 2
+SPARQ_FLAG_NO_REALLOC, SPARQ_FLAG_GQA_SHARED, SPARQ_FLAG_RAGGED_BATCH = 1, 2, 4
 SPARQ_ERR_APPEND_FULL, SPARQ_ERR_EMPTY_SEQ, SPARQ_ERR_IDX_TRUNCATED, SPARQ_ERR_BAD_SEQ_LEN = 1, 2, 4, 8
 SPARQ_OK, SPARQ_EINVAL, SPARQ_EUNSUPPORTED, SPARQ_EWORKSPACE, SPARQ_ELAUNCH = 0, -1, -2, -3, -4
 

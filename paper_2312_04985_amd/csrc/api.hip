@@ -20,7 +20,7 @@ int check_shape(const sparq_shape* s) {
   if (s->r < 1 || s->r > s->d_h || s->k < 1) return SPARQ_EINVAL;
   if (s->dtype != SPARQ_F16 && s->dtype != SPARQ_BF16) return SPARQ_EINVAL;
   if (s->S_max % 64 != 0) return SPARQ_EINVAL;
-  if (s->flags & ~(uint32_t)(SPARQ_FLAG_NO_REALLOC | SPARQ_FLAG_GQA_SHARED)) return SPARQ_EINVAL;
+  if (s->flags & ~(uint32_t)(SPARQ_FLAG_NO_REALLOC | SPARQ_FLAG_GQA_SHARED | SPARQ_FLAG_RAGGED_BATCH)) return SPARQ_EINVAL;
   if (s->d_h != 64 && s->d_h != 128 && s->d_h != 256) return SPARQ_EUNSUPPORTED;
   // element offsets inside one tensor are formed in size_t; the counts themselves stay in int32
   if ((int64_t)s->B * s->H > (int64_t)1 << 30) return SPARQ_EUNSUPPORTED;

@@ -53,11 +53,27 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   const Lds L = carve<DH>(smem, a.S_max);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-  // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of units so
-  // that the query heads of one KV group share an L2.
+  // Workgroup -> unit.  Workgroups are dealt round-robin to the 8 XCDs and started in index order.
+  // Default: every XCD gets a contiguous run of units, so the query heads of a KV group share an L2.
+  // With the ragged-batch hint (and no grouped heads): workgroup i serves the sequence with the
+  // (i / H)-th largest length, so the longest sequences start first and the short ones fill in behind.
   const int U = a.B * a.H;
   int u = blockIdx.x;
-  if ((U & 7) == 0) u = (u & 7) * (U >> 3) + (u >> 3);
+  if ((a.flags & 4u) && a.H == a.H_kv && a.B > 1 && a.B <= NT) {
+    int* lens = reinterpret_cast<int*>(L.keys);   // free until stage 1
+    if (tid < a.B) lens[tid] = a.seq_lens[tid];
+    __syncthreads();
+    if (tid < a.B) {
+      const int mine = lens[tid];
+      int rank = 0;
+      for (int j = 0; j < a.B; ++j) rank += (lens[j] > mine) || (lens[j] == mine && j < tid);
+      if (rank == u / a.H) L.sel.ctl[7] = tid;
+    }
+    __syncthreads();
+    u = L.sel.ctl[7] * a.H + u % a.H;
+  } else if ((U & 7) == 0) {
+    u = (u & 7) * (U >> 3) + (u >> 3);
+  }
   const int b = u / a.H, h = u - b * a.H;
   const int hk = h / (a.H / a.H_kv);
   const size_t kv_head = (size_t)b * a.H_kv + hk;

@@ -159,7 +159,7 @@ def compare_decode(b: Built, q: torch.Tensor, *, flags: int = 0, check_state: bo
         Kh, Vh = host_cache_codes(b, c.S_max)
     qh = W.to_codes(q)
     seq = b.seq_lens.numpy(); kps = None if b.k_per_seq is None else b.k_per_seq.numpy()
-    ref = O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags, k_per_seq=kps, want_z=True)
+    ref = O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags & 3, k_per_seq=kps, want_z=True)
     Kf = O.to_double(Kh, w.dtype_code); qf = O.to_double(qh, w.dtype_code)
 
     assert np.array_equal(chan.cpu().numpy(), ref.i1), "i1 (top-r channels) must match exactly"
@@ -168,7 +168,7 @@ def compare_decode(b: Built, q: torch.Tensor, *, flags: int = 0, check_state: bo
     # outputs are compared with the oracle run on the GPU's own position sets, so that a position
     # inside the uncompared band cannot pass for, or hide, an output error
     ref_g = ref if stats["exact_sets"] == stats["units"] else \
-        O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags, k_per_seq=kps, given_i2=gi)
+        O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags & 3, k_per_seq=kps, given_i2=gi)
     a_err = np.abs(alpha.cpu().numpy().astype(np.float64) - ref_g.alpha).max()
     assert a_err <= ALPHA_TOL, f"alpha error {a_err}"
     got = out.float().cpu().numpy().astype(np.float64)
@@ -228,7 +228,7 @@ def compare_sampled(b: Built, q: torch.Tensor, *, n_units: int = 48, flags: int 
     got_vm = np.stack([c.v_mean[divmod(int(p), w.H_kv)].cpu().numpy() for p in picks]).astype(np.float64)
     assert np.abs(got_vm - vbar).max() <= VMEAN_TOL, "v_mean"
 
-    ref = O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags, k_per_seq=kps, want_z=True)
+    ref = O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags & 3, k_per_seq=kps, want_z=True)
     Kf = O.to_double(Kh, w.dtype_code); qf = O.to_double(qh, w.dtype_code)
     assert np.array_equal(g_chan, ref.i1), "i1 (top-r channels) must match exactly"
     stride = ref.i2.shape[-1]
@@ -236,7 +236,7 @@ def compare_sampled(b: Built, q: torch.Tensor, *, n_units: int = 48, flags: int 
     ws = W.scaled(w, B=n, H=g, H_kv=1)
     stats = check_positions(g_idx[:, :, :stride], ref, Kf, qf, seq, kps, ws)
     ref_g = ref if stats["exact_sets"] == stats["units"] else \
-        O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags, k_per_seq=kps,
+        O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags & 3, k_per_seq=kps,
                        given_i2=np.ascontiguousarray(g_idx[:, :, :stride]))
     a_err = np.abs(g_alpha - ref_g.alpha).max()
     assert a_err <= ALPHA_TOL, f"alpha error {a_err}"

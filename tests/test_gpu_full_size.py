@@ -6,6 +6,7 @@ import sys
 import pytest
 import torch
 
+from paper_2312_04985_amd import binding as B
 from paper_2312_04985_amd import workloads as W
 
 import harness as Hn
@@ -27,7 +28,8 @@ def test_full_size_sampled(name, n_units, singles):
     b = Hn.build_cache(w, single_appends=singles, poison=None)
     say("   cache built:", tuple(b.cache.K.shape), "seq_lens", b.seq_lens[:8].tolist())
     q = W.draw_queries(w, b.K_src, b.seq_lens, n=1)[0]
-    stats = Hn.compare_sampled(b, q, n_units=n_units, seed=w.seed)
+    flags = B.SPARQ_FLAG_RAGGED_BATCH if w.ragged else 0           # as bench.py launches it
+    stats = Hn.compare_sampled(b, q, n_units=n_units, seed=w.seed, flags=flags)
     say("   ", stats)
     del b
     torch.cuda.empty_cache()

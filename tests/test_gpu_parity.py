@@ -61,6 +61,9 @@ def test_c4_large_batch_shape_reduced_batch():
 def test_c5_gemma_ragged_reduced_batch():
     run(W.scaled(C["c5_gemma_7b_ragged"], B=5, H=2, H_kv=2))
     run(W.scaled(C["c5_gemma_7b_ragged"], B=3, H=2, H_kv=2), v_offset=True, q_scale=0.002)
+    # the longest-first scheduling hint changes which workgroup serves which sequence, nothing else
+    run(W.scaled(C["c5_gemma_7b_ragged"], B=7, H=2, H_kv=2), flags=B.SPARQ_FLAG_RAGGED_BATCH)
+    run(W.scaled(C["c5_gemma_7b_ragged"], B=4, H=4, H_kv=2, S=3000, ragged=(5, 3000)), flags=B.SPARQ_FLAG_RAGGED_BATCH, v_offset=True, q_scale=0.002)
 
 
 def test_paper_microbenchmark_shape_reduced_batch():
