@@ -46,9 +46,12 @@ typedef enum { SPARQ_F16 = 0, SPARQ_BF16 = 1 } sparq_dtype;
 enum {
   /* y = y3: skip the blend of Step 3 (Section 4 omits it for grouped-query models) */
   SPARQ_FLAG_NO_REALLOC = 1u << 0,
-  /* one channel set and one position set per KV head from group sums (Section 4,
-   * "Grouped query attention").  Not built yet: returns SPARQ_EUNSUPPORTED.  The default
-   * treats every query head independently over its shared KV head. */
+  /* the paper's grouped-query rule (Section 4, "Grouped query attention"; Appendix B): one
+   * channel set per KV head from the group sum of |q|, one position set per KV head from the
+   * group sum of the approximate scores s-hat; tau, alpha and the exact attention stay per
+   * query head; idx_out / chan_out repeat the shared sets for every head of the group.
+   * Built for groups of 2 and 4 query heads (SPARQ_EUNSUPPORTED otherwise).  Without the flag
+   * every query head selects independently over its shared KV head. */
   SPARQ_FLAG_GQA_SHARED = 1u << 1,
   /* scheduling hint, no effect on results: the sequence lengths of the batch differ widely;
    * sparq_decode / sparq_decode_step then start the longest sequences first */

@@ -215,7 +215,9 @@ static void sparq_group(const group_job* J) {
     double l1_all = 0.0, l1_sel = 0.0;
     for (int c = 0; c < d_h; ++c) l1_all += fabs(qt[c]);
     for (int j = 0; j < r; ++j) l1_sel += fabs(qt[i1[j]]);
-    double tau = l1_all > 0.0 ? sqrt((double)d_h * l1_sel / l1_all) : sqrt((double)d_h);
+    /* no mass on the selected channels (q = 0, or in shared mode a head that is zero on the group's
+       channels): every logit is 0 whatever tau is; take sqrt(d_h) so that 0 / tau is defined */
+    double tau = l1_sel > 0.0 ? sqrt((double)d_h * l1_sel / l1_all) : sqrt((double)d_h);
     J->tau[t] = tau;
     for (int j = 0; j < r; ++j) J->i1[t * r + j] = i1[j];
 

@@ -108,23 +108,22 @@ int max_lds_bytes() {
   return cached;
 }
 
+// the paper's grouped-query rule is a kernel of its own; with one query head per KV head it is
+// the ordinary rule
+bool wants_shared(const sparq_shape* shape) {
+  return (shape->flags & SPARQ_FLAG_GQA_SHARED) && shape->H != shape->H_kv;
+}
+
 // enqueue one decode over `a` with the plan the shape calls for
 hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* workspace, hipStream_t s) {
-  int n_split;
-  if (!split_plan(shape, &n_split)) return launch_decode(a, shape->dtype, s);
-  const SplitLayout l = split_layout(shape, n_split);
-  char* w = static_cast<char*>(workspace);
-  SplitArgs sa;
-  sa.d = a;
-  sa.n_split = n_split;
-  sa.tmax_ws = reinterpret_cast<float*>(w + l.tmax);
-  sa.tau_ws = reinterpret_cast<float*>(w + l.tau);
-  sa.alpha_ws = reinterpret_cast<float*>(w + l.alpha);
-  sa.keys_ws = reinterpret_cast<uint32_t*>(w + l.keys);
-  sa.list_ws = reinterpret_cast<int32_t*>(w + l.list);
-  sa.part_ws = reinterpret_cast<float*>(w + l.part);
+  int n_split = 0;
+  const bool shared = wants_shared(shape);
+  const bool split = !shared && split_plan(shape, &n_split);
+  if (!shared && !split) return launch_decode(a, shape->dtype, s);
+  DecodeArgs d = a;
   if (a.k_new) {
-    // the one-launch step has no split form: append into the *_next state, then decode from it
+    // only the one-workgroup-per-head kernel has the append built in: append into the *_next state
+    // with the append kernel, then decode from that state
     AppendArgs ap;
     ap.K = a.K; ap.Kt = a.Kt; ap.V = a.V; ap.v_mean = const_cast<float*>(a.v_mean); ap.seq_lens = const_cast<int32_t*>(a.seq_lens);
     ap.v_mean_out = a.v_mean_next; ap.seq_lens_out = a.seq_lens_next;
@@ -132,17 +131,34 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
     ap.B = a.B; ap.H_kv = a.H_kv; ap.S_max = a.S_max; ap.d_h = a.d_h; ap.n_new = 1;
     hipError_t e = launch_append(ap, shape->dtype, s);
     if (e != hipSuccess) return e;
-    sa.d.v_mean = a.v_mean_next; sa.d.seq_lens = a.seq_lens_next;
-    sa.d.k_new = nullptr; sa.d.v_new = nullptr; sa.d.v_mean_next = nullptr; sa.d.seq_lens_next = nullptr;
+    d.v_mean = a.v_mean_next; d.seq_lens = a.seq_lens_next;
+    d.k_new = nullptr; d.v_new = nullptr; d.v_mean_next = nullptr; d.seq_lens_next = nullptr;
   }
+  if (shared) return launch_decode_shared(d, shape->dtype, s);
+  const SplitLayout l = split_layout(shape, n_split);
+  char* w = static_cast<char*>(workspace);
+  SplitArgs sa;
+  sa.d = d;
+  sa.n_split = n_split;
+  sa.tmax_ws = reinterpret_cast<float*>(w + l.tmax);
+  sa.tau_ws = reinterpret_cast<float*>(w + l.tau);
+  sa.alpha_ws = reinterpret_cast<float*>(w + l.alpha);
+  sa.keys_ws = reinterpret_cast<uint32_t*>(w + l.keys);
+  sa.list_ws = reinterpret_cast<int32_t*>(w + l.list);
+  sa.part_ws = reinterpret_cast<float*>(w + l.part);
   return launch_decode_split(sa, shape->dtype, s);
 }
 
-// the one-workgroup-per-unit kernel keeps one 4-byte key per cached position in LDS
+// every decode kernel keeps one 4-byte key per cached position in LDS
 bool decode_supported(const sparq_shape* shape) {
   int n_split;
-  if (split_plan(shape, &n_split)) return split_select_lds_bytes(shape->S_max) <= (size_t)max_lds_bytes();
-  return decode_lds_bytes(shape->S_max, shape->d_h) <= (size_t)max_lds_bytes();
+  const size_t lds_max = (size_t)max_lds_bytes();
+  if (wants_shared(shape)) {
+    const size_t need = decode_shared_lds_bytes(shape->S_max, shape->d_h, shape->H / shape->H_kv);
+    return need != 0 && need <= lds_max;
+  }
+  if (split_plan(shape, &n_split)) return split_select_lds_bytes(shape->S_max) <= lds_max;
+  return decode_lds_bytes(shape->S_max, shape->d_h) <= lds_max;
 }
 
 }  // namespace
@@ -190,7 +206,6 @@ int sparq_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
   if (idx_out && idx_stride < 1) return SPARQ_EINVAL;
   rc = check_workspace(shape, workspace, workspace_bytes);
   if (rc != SPARQ_OK) return rc;
-  if (shape->flags & SPARQ_FLAG_GQA_SHARED) return SPARQ_EUNSUPPORTED;
   if (!decode_supported(shape)) return SPARQ_EUNSUPPORTED;
   DecodeArgs a;
   a.K = cache->K; a.Kt = cache->Kt; a.V = cache->V; a.v_mean = cache->v_mean; a.seq_lens = cache->seq_lens;
@@ -217,7 +232,6 @@ int sparq_decode_step(const sparq_shape* shape, const sparq_cache* cache, const 
   if (idx_out && idx_stride < 1) return SPARQ_EINVAL;
   rc = check_workspace(shape, workspace, workspace_bytes);
   if (rc != SPARQ_OK) return rc;
-  if (shape->flags & SPARQ_FLAG_GQA_SHARED) return SPARQ_EUNSUPPORTED;
   if (!decode_supported(shape)) return SPARQ_EUNSUPPORTED;
   DecodeArgs a;
   a.K = cache->K; a.Kt = cache->Kt; a.V = cache->V; a.v_mean = cache->v_mean; a.seq_lens = cache->seq_lens;

@@ -244,7 +244,9 @@ __device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wsum, 
 // were measured and are not faster: the sweep is bound by its arithmetic, not by the barrier.)
 // `list` may be the key array itself: the list overwrites it from the front; a write never lands
 // beyond the position it records and all reads of a sweep precede its writes (the scan's barrier).
-// Ends with a barrier that also publishes the list.  esc = log2(e) / tau.
+// Ends with a barrier that also publishes the list.  esc = log2(e) / tau.  With WITH_ALPHA = false only
+// the list is produced (the grouped-query kernel gets alpha per query head elsewhere) and 0 is returned.
+template <bool WITH_ALPHA = true>
 __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t* list, int S, uint32_t pmask,
                                                   uint32_t pval, int need, float dmax, float esc, int32_t* idx_out,
                                                   int idx_stride, const SelectLds& sl, int tid, int lane, int wave) {
@@ -282,7 +284,7 @@ __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t
     for (int e = 0; e < 8; ++e) {
       const bool valid = (c * 8 + e) < S && c < n_chunks;
       if (valid) {
-        const float w = exp2f((key_to_float(kx[e]) - dmax) * esc);
+        const float w = WITH_ALPHA ? exp2f((key_to_float(kx[e]) - dmax) * esc) : 0.0f;
         zsum += w;
         bool take = (gt_bits >> e) & 1u;
         if ((eq_bits >> e) & 1u) { take = eq_before < (uint32_t)need; ++eq_before; }
@@ -296,6 +298,10 @@ __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t
     }
     run_gt += total & 0xffffu;
     run_eq += total >> 16;
+  }
+  if (!WITH_ALPHA) {
+    __syncthreads();
+    return 0.0f;
   }
   zsum = wave_sum(zsum); asum = wave_sum(asum);
   if (lane == 0) { sl.red[wave] = zsum; sl.red[NW + wave] = asum; }

@@ -54,8 +54,10 @@ struct SplitArgs {
 // LDS bytes the fused decode kernel needs for a cache of S_max rows and head dimension d_h
 size_t decode_lds_bytes(int S_max, int d_h);
 size_t split_select_lds_bytes(int S_max);
+size_t decode_shared_lds_bytes(int S_max, int d_h, int g);   // 0: no grouped-query kernel for this shape
 
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s);
+hipError_t launch_decode_shared(const DecodeArgs& a, int dtype, hipStream_t s);
 hipError_t launch_decode_split(const SplitArgs& a, int dtype, hipStream_t s);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t s);
 hipError_t launch_dense(const DenseArgs& a, int dtype, hipStream_t s);

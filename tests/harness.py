@@ -140,6 +140,49 @@ def check_positions(gpu_idx: np.ndarray, ref: O.SparqResult, Kf: np.ndarray, qf:
     return dict(units=Bn * H, exact_sets=exact, uncompared_score_gap=skipped_a, uncompared_fp32_bound=skipped_b)
 
 
+def check_positions_shared(gpu_idx: np.ndarray, ref: O.SparqResult, Kf: np.ndarray, qf: np.ndarray, seq, kps, w) -> dict:
+    """Index-set parity under the grouped-query rule: all heads of a group report the same list; the
+    list is the top-k of the group score sum_h s-hat_h.  Positions whose oracle score is within
+    1e-6 + 2 * (2 E + 3e-6) * score of the threshold score are not compared, E being the worst-case
+    fp32 error of a head's logit (r * 2^-24 * sum_j |q_j K_ij| / tau): an error E of a logit moves
+    s-hat by at most about 2 E of itself (numerator and normaliser)."""
+    Bn, H = gpu_idx.shape[:2]
+    g = w.H // w.H_kv
+    exact = 0; skipped = 0; E_max = 0.0
+    for b in range(Bn):
+        S = int(seq[b]); kq = min(int(kps[b]) if kps is not None else w.k, S)
+        for hk in range(w.H_kv):
+            heads = range(hk * g, (hk + 1) * g)
+            got = gpu_idx[b, hk * g]
+            for h in heads:
+                assert np.array_equal(gpu_idx[b, h], got), "heads of a group must report one list"
+            assert (got[kq:] == -1).all()
+            sel = got[:kq]
+            assert (sel >= 0).all() and (sel < S).all() and (np.diff(sel) > 0).all()
+            score = np.zeros(S); E = 0.0
+            for h in heads:
+                z = ref.z[b, h, :S]
+                e = np.exp(z - z.max()); score += e / e.sum()
+                i1 = ref.i1[b, h]
+                absdot = np.abs(Kf[b, hk, :S][:, i1] * qf[b, h, i1][None, :]).sum(axis=1)
+                E = max(E, 1.01 * w.r * 2.0 ** -24 * absdot.max() / ref.tau[b, h])
+            E_max = max(E_max, E)
+            if np.array_equal(sel, ref.i2[b, hk * g, :kq]):
+                exact += 1
+                continue
+            assert kq < S
+            order = np.sort(score)[::-1]
+            s_in, s_out = order[kq - 1], order[kq]
+            rel = 2 * (2 * E + 3e-6)
+            got_mask = np.zeros(S, dtype=bool); got_mask[sel] = True
+            sure_in = score - s_out > 1e-6 + rel * np.maximum(score, s_out)
+            sure_out = s_in - score > 1e-6 + rel * np.maximum(score, s_in)
+            assert got_mask[sure_in].all() and not got_mask[sure_out].any(), f"group-score check failed at ({b},{hk})"
+            skipped += int(S - sure_in.sum() - sure_out.sum())
+    return dict(units=Bn * w.H_kv, exact_sets=exact, uncompared_score_gap=skipped, uncompared_fp32_bound=skipped,
+                logit_err_bound=E_max)
+
+
 def compare_decode(b: Built, q: torch.Tensor, *, flags: int = 0, check_state: bool = True) -> dict:
     """Run sparq_decode and dense_decode on the GPU and the oracle on the host; assert parity."""
     w, c = b.w, b.cache
@@ -164,13 +207,18 @@ def compare_decode(b: Built, q: torch.Tensor, *, flags: int = 0, check_state: bo
 
     assert np.array_equal(chan.cpu().numpy(), ref.i1), "i1 (top-r channels) must match exactly"
     gi = idx.cpu().numpy()
-    stats = check_positions(gi, ref, Kf, qf, seq, kps, w)
+    shared = bool(flags & 2) and w.H != w.H_kv
+    stats = (check_positions_shared if shared else check_positions)(gi, ref, Kf, qf, seq, kps, w)
     # outputs are compared with the oracle run on the GPU's own position sets, so that a position
     # inside the uncompared band cannot pass for, or hide, an output error
     ref_g = ref if stats["exact_sets"] == stats["units"] else \
         O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags & 3, k_per_seq=kps, given_i2=gi)
     a_err = np.abs(alpha.cpu().numpy().astype(np.float64) - ref_g.alpha).max()
-    assert a_err <= ALPHA_TOL, f"alpha error {a_err}"
+    # The grouped-query kernel does not keep G x S logits: alpha's numerator comes from logits
+    # recomputed on the gathered key rows, the normaliser from the streamed ones.  The two fp32
+    # evaluations of one logit differ by up to 2 E, which no longer cancels in the ratio.
+    a_tol = ALPHA_TOL + (2 * stats["logit_err_bound"] if shared else 0.0)
+    assert a_err <= a_tol, f"alpha error {a_err} > {a_tol}"
     got = out.float().cpu().numpy().astype(np.float64)
     err = np.abs(got - ref_g.y)
     assert (err <= out_tolerance(w.dtype_code, ref_g.y)).all(), f"output error {err.max()}"

@@ -184,7 +184,7 @@ def test_long_running_mean_drift():
 # ------------------------------------------------------------------ host-side refusal with a GPU present
 
 def test_unsupported_requests_are_refused():
-    w = W.Workload("refuse", 1, 4, 2, 128, 128, 16, 8, "f16", seed=23)
+    w = W.Workload("refuse", 1, 8, 1, 128, 128, 16, 8, "f16", seed=23)     # groups of 8 heads: no shared-rule kernel
     b = Hn.build_cache(w)
     q = W.draw_queries(w, b.K_src, b.seq_lens)[0]
     b.cache.with_params(16, 8, B.SPARQ_FLAG_GQA_SHARED)
@@ -193,6 +193,62 @@ def test_unsupported_requests_are_refused():
     assert e.value.status == B.SPARQ_EUNSUPPORTED
     with pytest.raises(ValueError):
         b.cache.with_params(16, 8).decode(q.cpu())
+
+
+# ------------------------------------------------------------------ the paper's grouped-query rule
+
+@pytest.mark.parametrize("name,kw,qs", [
+    ("g4_f16", dict(B=2, H=8, H_kv=2, d_h=128, S=3000, r=16, k=256, dtype="f16"), 0.01),
+    ("g2_bf16_d256", dict(B=2, H=4, H_kv=2, d_h=256, S=1500, r=64, k=100, dtype="bf16"), 0.003),
+    ("g4_planted_long", dict(B=1, H=8, H_kv=2, d_h=128, S=20000, r=32, k=1024, dtype="bf16"), 1.0),
+    ("g4_short_d64", dict(B=3, H=4, H_kv=1, d_h=64, S=70, r=8, k=100, dtype="f16"), 0.05),
+])
+def test_grouped_query_shared_selection(name, kw, qs):
+    """SPARQ_FLAG_GQA_SHARED: one channel set and one position set per KV head from the group sums
+    (Section 4, 'Grouped query attention'), tau / alpha / attention per query head."""
+    w = W.Workload(name, seed=50, **kw)
+    seq = torch.tensor([max(1, w.S - 37 * i) for i in range(w.B)], dtype=torch.int32)
+    st = run(w, flags=B.SPARQ_FLAG_GQA_SHARED, q_scale=qs, v_offset=True, n_q=2, seq_lens=seq)
+    run(w, flags=B.SPARQ_FLAG_GQA_SHARED | B.SPARQ_FLAG_NO_REALLOC, q_scale=qs, v_offset=True, seq_lens=seq)
+    # with one query head per KV head the flag changes nothing
+    w1 = W.scaled(w, H=w.H_kv, S=min(w.S, 2000))
+    b = Hn.build_cache(w1, v_offset=True)
+    q = W.draw_queries(w1, b.K_src, b.seq_lens, q_scale=qs)[0]
+    o0 = b.cache.with_params(w1.r, w1.k, 0).decode(q)
+    o1 = b.cache.with_params(w1.r, w1.k, B.SPARQ_FLAG_GQA_SHARED).decode(q)
+    assert torch.equal(o0.view(torch.int16), o1.view(torch.int16))
+
+
+def test_grouped_query_shared_step_and_ties():
+    """The one-call step under the shared rule (append kernel + decode), and all-identical keys
+    (every group score ties: the k lowest positions, alpha = k / S for every head)."""
+    w = W.Workload("g4_step", 2, 8, 2, 128, 900, 16, 64, "f16", seed=51)
+    b = Hn.build_cache(w, v_offset=True)
+    b.cache.with_params(w.r, w.k, B.SPARQ_FLAG_GQA_SHARED)
+    kn, vn = W.draw_kv(W.scaled(w, seed=79), "cuda", n_rows=1, v_offset=True)
+    q = W.draw_queries(w, b.K_src, b.seq_lens, q_scale=0.02)[0].clone()
+    q[:, 1] = 0                       # an all-zero head inside a group: tau = sqrt(d_h), uniform s-hat
+    q[:, 4:8, 5] = 0                  # a head with no mass on the group's channels: logits all 0
+    q[:, 6] = 0; q[:, 6, 5] = 1e-3
+    out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q)
+    torch.cuda.synchronize()
+    assert b.cache.seq_lens.cpu().tolist() == [901, 901] and b.cache.error_flags() == 0
+    grown = Hn.Built(w, b.cache, torch.cat([b.K_src, kn], dim=2), torch.cat([b.V_src, vn], dim=2), b.seq_lens + 1, None)
+    st = Hn.compare_decode(grown, q, flags=B.SPARQ_FLAG_GQA_SHARED)
+    say(st)
+    ref_out = b.cache.decode(q)
+    assert torch.equal(out.view(torch.int16), ref_out.view(torch.int16))
+    # ties
+    wt = W.Workload("g4_ties", 1, 4, 1, 128, 500, 16, 50, "f16", seed=52)
+    t = Hn.build_cache(wt)
+    t.K_src[:] = t.K_src[:, :, :1]
+    t = Hn.Built(wt, DecodeCache(1, 4, 1, 512, 128, 16, 50, wt.torch_dtype, flags=B.SPARQ_FLAG_GQA_SHARED), t.K_src, t.V_src, t.seq_lens, None)
+    t.cache.append(t.K_src, t.V_src)
+    q = W.draw_queries(wt, t.K_src, t.seq_lens)[0]
+    out, alpha, idx, chan = t.cache.decode(q, aux=True)
+    assert torch.equal(idx.cpu(), torch.arange(50, dtype=torch.int32).expand(1, 4, 50))
+    assert torch.allclose(alpha.cpu(), torch.full((1, 4), 0.1), atol=1e-5)   # recomputed-logit numerator
+    Hn.compare_decode(t, q, flags=B.SPARQ_FLAG_GQA_SHARED)
 
 
 # ------------------------------------------------------------------ the one-launch decode step

@@ -358,6 +358,21 @@ def test_shared_group_selection_follows_appendix_b():
     assert np.array_equal(a.i2, b.i2) and np.abs(a.y - b.y).max() < 1e-14
 
 
+def test_shared_group_head_without_mass_on_the_groups_channels():
+    """A head that is zero on every channel the group selects has all-zero approximate logits:
+    uniform s-hat (1/S each) whatever tau is, so its alpha is k/S, and the group's positions are
+    decided by the other heads alone."""
+    c = rand_case(54, B=1, H=2, H_kv=1, S=24, d_h=8, v_shift=0.3)
+    q = c["q"].copy()
+    q[0, 1] = 0.0; q[0, 0, 6] = 0.0; q[0, 1, 6] = 1e-3       # channel 6 carries the smallest group sum
+    qc, _ = codes_from_floats(q, F16)
+    res = O.sparq_decode(c["Kc"], c["Vc"], qc, c["seq"], r=3, k=6, dtype=F16, flags=O.GQA_SHARED, want_z=True)
+    assert 6 not in res.i1[0, 0].tolist()
+    assert np.all(res.z[0, 1, :24] == 0.0) and np.isfinite(res.tau[0, 1])
+    assert res.alpha[0, 1] == pytest.approx(6 / 24, rel=1e-14)
+    assert res.i2[0, 1].tolist() == np.sort(np.argsort(-res.z[0, 0, :24], kind="stable")[:6]).tolist()
+
+
 # ---------------------------------------------------------------- cache maintenance
 
 def test_kv_append_definition():
