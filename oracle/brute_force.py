@@ -27,8 +27,10 @@ def top(values, count):
     return sorted(order[:count])
 
 
-def sparq(q, K, V, r, k, realloc=True):
-    """Steps 1-3 for one query head.  q: [d_h], K, V: [S][d_h] (lists of floats)."""
+def sparq(q, K, V, r, k, realloc=True, tau_mode="l1", local_window=0):
+    """Steps 1-3 for one query head.  q: [d_h], K, V: [S][d_h] (lists of floats).
+    tau_mode: "l1" (Eq. 7), "sqrt_dh" or "sqrt_r" (the fixed temperatures of the ablation in
+    Section 5.3); local_window: that many most recent positions are always kept."""
     d_h, S = len(q), len(K)
     k = min(k, S)
     # Step 1
@@ -36,10 +38,12 @@ def sparq(q, K, V, r, k, realloc=True):
     l1_all = math.fsum(abs(x) for x in q)
     l1_sel = math.fsum(abs(q[c]) for c in i1)
     tau = math.sqrt(d_h * l1_sel / l1_all) if l1_all > 0 else math.sqrt(d_h)
+    tau = {"l1": tau, "sqrt_dh": math.sqrt(d_h), "sqrt_r": math.sqrt(r)}[tau_mode]
     z = [math.fsum(q[c] * K[i][c] for c in i1) / tau for i in range(S)]
     s_hat = softmax(z)
     # Step 2
-    i2 = top(s_hat, k)   # the paper's literal rule: top-k of the softmax output
+    n_local = min(local_window, k)
+    i2 = top(s_hat[:S - n_local], k - n_local) + list(range(S - n_local, S))   # top-k of the softmax output
     sub = softmax([math.fsum(q[c] * K[i][c] for c in range(d_h)) / math.sqrt(d_h) for i in i2])
     y3 = [math.fsum(sub[n] * V[i][c] for n, i in enumerate(i2)) for c in range(d_h)]
     # Step 3

@@ -38,7 +38,7 @@
 #endif
 
 enum { ORACLE_F16 = 0, ORACLE_BF16 = 1 };
-enum { ORACLE_NO_REALLOC = 1, ORACLE_GQA_SHARED = 2 };
+enum { ORACLE_NO_REALLOC = 1, ORACLE_GQA_SHARED = 2, ORACLE_TAU_SQRT_DH = 8, ORACLE_TAU_SQRT_R = 16 };
 
 /* ---- exact widening of the 16-bit storage formats -------------------------------- */
 
@@ -168,7 +168,7 @@ int oracle_dense_decode(int B, int H, int H_kv, int S_max, int d_h, int dtype,
 /* ---- SparQ, one KV head with its g query heads ----------------------------------- */
 
 typedef struct {
-  int S_max, d_h, r, dtype, g, S, k_eff, k_stride;
+  int S_max, d_h, r, dtype, g, S, k_eff, k_stride, local_window;
   unsigned flags;
   const uint16_t *K, *V;          /* this KV head: [S_max, d_h] */
   const uint16_t* q;              /* the g query heads of the group: [g, d_h] */
@@ -218,6 +218,9 @@ static void sparq_group(const group_job* J) {
     /* no mass on the selected channels (q = 0, or in shared mode a head that is zero on the group's
        channels): every logit is 0 whatever tau is; take sqrt(d_h) so that 0 / tau is defined */
     double tau = l1_sel > 0.0 ? sqrt((double)d_h * l1_sel / l1_all) : sqrt((double)d_h);
+    /* the two fixed temperatures of the ablation (Section 5.3 'Approximate softmax temperature') */
+    if (J->flags & ORACLE_TAU_SQRT_DH) tau = sqrt((double)d_h);
+    if (J->flags & ORACLE_TAU_SQRT_R) tau = sqrt((double)r);
     J->tau[t] = tau;
     for (int j = 0; j < r; ++j) J->i1[t * r + j] = i1[j];
 
@@ -242,6 +245,11 @@ static void sparq_group(const group_job* J) {
 
   if (!(J->flags & ORACLE_NO_REALLOC)) mean_value(J->V, S, d_h, dtype, vbar);
 
+  /* Local window (Appendix 'Experimental setup', l): the l most recent positions are always selected,
+     the other k - l are the best-scoring of the positions before them. */
+  const int n_local = J->local_window < J->k_eff ? J->local_window : J->k_eff;
+  const int n_top = J->k_eff - n_local, S_old = S - n_local;
+
   /* Steps 2 and 3, per query head; positions shared across the group in shared mode */
   for (int t = 0; t < g; ++t) {
     int n_pos = J->k_eff;
@@ -257,11 +265,13 @@ static void sparq_group(const group_job* J) {
           score[i] = 0.0;
           for (int u = 0; u < g; ++u) score[i] += shat[(size_t)u * S + i];
         }
-        top_indices(score, S, n_pos, pos);
+        top_indices(score, S_old, n_top, pos);
+        for (int i = 0; i < n_local; ++i) pos[n_top + i] = S_old + i;
       }
     } else {
       /* top-k of s-hat for one head == top-k of its logits z */
-      top_indices(zrow + (size_t)t * S, S, n_pos, pos);
+      top_indices(zrow + (size_t)t * S, S_old, n_top, pos);
+      for (int i = 0; i < n_local; ++i) pos[n_top + i] = S_old + i;
     }
     for (int n = 0; n < J->k_stride; ++n)
       J->i2[(size_t)t * J->k_stride + n] = n < n_pos ? pos[n] : -1;
@@ -285,17 +295,19 @@ static void sparq_group(const group_job* J) {
  *   K, V      [B, H_kv, S_max, d_h]  raw 16-bit codes (dtype: 0 = binary16, 1 = bfloat16)
  *   q         [B, H, d_h]
  *   seq_lens  [B]; k_per_seq nullable [B] (overrides k); given_i2 nullable [B, H, k_stride]
+ *   local_window  l >= 0: the min(l, k_b, S_b) most recent positions are selected unconditionally
  *   y [B,H,d_h], alpha [B,H], tau [B,H], i1 [B,H,r] ascending, i2 [B,H,k_stride] ascending, -1 padded,
  *   z nullable [B,H,S_max] (approximate logits; entries >= S set to 0)
  * Returns 0, or a negative code for invalid arguments.
  */
-int oracle_sparq_decode(int B, int H, int H_kv, int S_max, int d_h, int r, int k, int dtype,
+int oracle_sparq_decode(int B, int H, int H_kv, int S_max, int d_h, int r, int k, int local_window, int dtype,
                         unsigned flags, const uint16_t* K, const uint16_t* V, const uint16_t* q,
                         const int32_t* seq_lens, const int32_t* k_per_seq, const int32_t* given_i2,
                         int k_stride, double* y, double* alpha, double* tau, int32_t* i1,
                         int32_t* i2, double* z) {
   if (B < 1 || H < 1 || H_kv < 1 || H % H_kv || d_h < 1 || S_max < 1) return -1;
-  if (r < 1 || r > d_h || k < 1 || k_stride < 1) return -1;
+  if (r < 1 || r > d_h || k < 1 || k_stride < 1 || local_window < 0) return -1;
+  if ((flags & ORACLE_TAU_SQRT_DH) && (flags & ORACLE_TAU_SQRT_R)) return -1;
   if (dtype != ORACLE_F16 && dtype != ORACLE_BF16) return -1;
   for (int b = 0; b < B; ++b) {
     int kb = k_per_seq ? k_per_seq[b] : k;
@@ -322,7 +334,7 @@ int oracle_sparq_decode(int B, int H, int H_kv, int S_max, int d_h, int r, int k
       }
       group_job J;
       J.S_max = S_max; J.d_h = d_h; J.r = r; J.dtype = dtype; J.g = g; J.S = S;
-      J.k_eff = kb < S ? kb : S; J.k_stride = k_stride; J.flags = flags;
+      J.k_eff = kb < S ? kb : S; J.k_stride = k_stride; J.flags = flags; J.local_window = local_window;
       J.K = K + kv; J.V = V + kv; J.q = q + unit * d_h;
       J.given_i2 = given_i2 ? given_i2 + unit * k_stride : NULL;
       J.y = y + unit * d_h; J.alpha = alpha + unit; J.tau = tau + unit;

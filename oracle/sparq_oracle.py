@@ -18,6 +18,7 @@ from . import build as _build
 
 F16, BF16 = 0, 1
 NO_REALLOC, GQA_SHARED = 1, 2
+TAU_SQRT_DH, TAU_SQRT_R = 8, 16
 
 _lib = None
 
@@ -31,7 +32,7 @@ def lib() -> ctypes.CDLL:
         L.oracle_to_double.argtypes = [c_int, vp, c_long, vp]
         L.oracle_mean_value.argtypes = [c_int, c_int, c_int, c_int, c_int, vp, vp, vp]
         L.oracle_dense_decode.argtypes = [c_int] * 6 + [vp] * 5
-        L.oracle_sparq_decode.argtypes = [c_int] * 8 + [c_uint] + [vp] * 6 + [c_int] + [vp] * 6
+        L.oracle_sparq_decode.argtypes = [c_int] * 9 + [c_uint] + [vp] * 6 + [c_int] + [vp] * 6
         L.oracle_num_threads.restype = c_int
         _lib = L
     return _lib
@@ -78,7 +79,7 @@ class SparqResult:
 
 
 def sparq_decode(K, V, q, seq_lens, *, r, k, dtype, flags=0, k_per_seq=None, given_i2=None,
-                 want_z=False) -> SparqResult:
+                 want_z=False, local_window=0) -> SparqResult:
     """SparQ decode step (Section 4, Steps 1-3) for a whole batch."""
     B, H_kv, S_max, d_h = K.shape
     H = q.shape[1]
@@ -94,7 +95,7 @@ def sparq_decode(K, V, q, seq_lens, *, r, k, dtype, flags=0, k_per_seq=None, giv
     y = np.empty((B, H, d_h)); alpha = np.empty((B, H)); tau = np.empty((B, H))
     i1 = np.empty((B, H, r), dtype=np.int32); i2 = np.empty((B, H, k_stride), dtype=np.int32)
     z = np.empty((B, H, S_max)) if want_z else None
-    rc = lib().oracle_sparq_decode(B, H, H_kv, S_max, d_h, r, k, dtype, flags, _ptr(K), _ptr(V), _ptr(q),
+    rc = lib().oracle_sparq_decode(B, H, H_kv, S_max, d_h, r, k, local_window, dtype, flags, _ptr(K), _ptr(V), _ptr(q),
                                    _ptr(seq_lens), _ptr(kps), _ptr(given_i2), k_stride,
                                    _ptr(y), _ptr(alpha), _ptr(tau), _ptr(i1), _ptr(i2), _ptr(z))
     if rc != 0:

@@ -373,6 +373,60 @@ def test_shared_group_head_without_mass_on_the_groups_channels():
     assert res.i2[0, 1].tolist() == np.sort(np.argsort(-res.z[0, 0, :24], kind="stable")[:6]).tolist()
 
 
+# ---------------------------------------------------------------- ablation switches
+
+@pytest.mark.parametrize("flag,mode", [(O.TAU_SQRT_DH, "sqrt_dh"), (O.TAU_SQRT_R, "sqrt_r")])
+def test_fixed_temperatures_of_the_ablation(flag, mode):
+    """Section 5.3 'Approximate softmax temperature': tau = sqrt(d_h) and tau = sqrt(r).  The logits
+    scale by tau_l1 / tau against the default run, the position set is the same (one head: a positive
+    rescaling keeps the order), and the brute force agrees."""
+    c = rand_case(71, S=40, d_h=16, v_shift=0.5)
+    r, k = 4, 9
+    base = O.sparq_decode(c["Kc"], c["Vc"], c["qc"], c["seq"], r=r, k=k, dtype=F16, want_z=True)
+    res = O.sparq_decode(c["Kc"], c["Vc"], c["qc"], c["seq"], r=r, k=k, dtype=F16, flags=flag, want_z=True)
+    fixed = math.sqrt(16) if mode == "sqrt_dh" else math.sqrt(r)
+    assert res.tau[0, 0] == pytest.approx(fixed, rel=1e-15)
+    assert np.allclose(res.z[0, 0] * fixed, base.z[0, 0] * base.tau[0, 0], rtol=1e-13, atol=1e-13)
+    assert np.array_equal(res.i2, base.i2) and np.array_equal(res.i1, base.i1)
+    bf = BF.sparq(c["q"][0, 0].tolist(), c["K"][0, 0].tolist(), c["V"][0, 0].tolist(), r, k, tau_mode=mode)
+    assert res.alpha[0, 0] == pytest.approx(bf["alpha"], rel=1e-12)
+    assert np.abs(res.y[0, 0] - np.array(bf["y"])).max() < 1e-12
+    # a hotter softmax (larger tau) spreads the mass: alpha of the same set shrinks with tau
+    if mode == "sqrt_dh":
+        assert res.alpha[0, 0] <= base.alpha[0, 0] + 1e-15
+    with pytest.raises(ValueError):
+        O.sparq_decode(c["Kc"], c["Vc"], c["qc"], c["seq"], r=r, k=k, dtype=F16, flags=O.TAU_SQRT_DH | O.TAU_SQRT_R)
+
+
+def test_local_window_keeps_the_most_recent_positions():
+    """Experimental-setup table, 'Local window l': the l most recent positions are always selected and
+    the other k - l come from the scores of the older ones.  l = 0 is the plain rule, l >= k keeps the
+    last k positions only, and r = d_h turns alpha into the exact mass of the kept set."""
+    c = rand_case(72, S=30, d_h=8, v_shift=0.5)
+    r, k = 3, 8
+    q, K, V = c["q"][0, 0], c["K"][0, 0], c["V"][0, 0]
+    args = dict(r=r, k=k, dtype=F16)
+    plain = O.sparq_decode(c["Kc"], c["Vc"], c["qc"], c["seq"], **args)
+    assert np.array_equal(O.sparq_decode(c["Kc"], c["Vc"], c["qc"], c["seq"], local_window=0, **args).i2, plain.i2)
+    for l in (1, 3, 8, 20):
+        res = O.sparq_decode(c["Kc"], c["Vc"], c["qc"], c["seq"], local_window=l, want_z=True, **args)
+        n_local = min(l, k)
+        i2 = res.i2[0, 0].tolist()
+        assert i2[k - n_local:] == list(range(30 - n_local, 30)) and len(set(i2)) == k and i2 == sorted(i2)
+        older = np.sort(np.argsort(-res.z[0, 0, :30 - n_local], kind="stable")[:k - n_local]).tolist()
+        assert i2[:k - n_local] == older
+        bf = BF.sparq(q.tolist(), K.tolist(), V.tolist(), r, k, local_window=l)
+        assert i2 == bf["i2"] and res.alpha[0, 0] == pytest.approx(bf["alpha"], rel=1e-12)
+        assert np.abs(res.y[0, 0] - np.array(bf["y"])).max() < 1e-12
+    full = O.sparq_decode(c["Kc"], c["Vc"], c["qc"], c["seq"], r=8, k=k, dtype=F16, local_window=5)
+    s = scipy_softmax(K @ q / math.sqrt(8))
+    assert full.alpha[0, 0] == pytest.approx(s[full.i2[0, 0]].sum(), rel=1e-12)
+    # grouped-query rule: the window is shared like the rest of the list
+    cg = rand_case(73, H=2, H_kv=1, S=30, d_h=8)
+    rg = O.sparq_decode(cg["Kc"], cg["Vc"], cg["qc"], cg["seq"], r=3, k=8, dtype=F16, flags=O.GQA_SHARED, local_window=3)
+    assert np.array_equal(rg.i2[0, 0], rg.i2[0, 1]) and rg.i2[0, 0, -3:].tolist() == [27, 28, 29]
+
+
 # ---------------------------------------------------------------- cache maintenance
 
 def test_kv_append_definition():
