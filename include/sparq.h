@@ -55,7 +55,11 @@ enum {
   SPARQ_FLAG_GQA_SHARED = 1u << 1,
   /* scheduling hint, no effect on results: the sequence lengths of the batch differ widely;
    * sparq_decode / sparq_decode_step then start the longest sequences first */
-  SPARQ_FLAG_RAGGED_BATCH = 1u << 2
+  SPARQ_FLAG_RAGGED_BATCH = 1u << 2,
+  /* the fixed temperatures of the paper's ablation (Section 5.3, "Approximate softmax
+   * temperature") in place of Eq. (7): tau = sqrt(d_h), or tau = sqrt(r).  At most one of the two. */
+  SPARQ_FLAG_TAU_SQRT_DH = 1u << 3,
+  SPARQ_FLAG_TAU_SQRT_R = 1u << 4
 };
 
 /* bits of the device-side error word (sparq_async_error) */
@@ -72,6 +76,10 @@ typedef struct {
   int32_t k;      /* >= 1; clamped per sequence to S_b */
   int32_t dtype;  /* sparq_dtype of K, Kt, V, q and out */
   uint32_t flags;
+  /* l >= 0 (the "local window" of the paper's experimental-setup table): the min(l, k_b, S_b) most
+   * recent positions are selected unconditionally and the other k_b - l are the best-scoring of the
+   * older positions; alpha sums s-hat over the whole set.  0 = the plain top-k rule. */
+  int32_t local_window;
 } sparq_shape;
 
 typedef struct {

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(HERE, "libsparq.so")
 
 SPARQ_F16, SPARQ_BF16 = 0, 1
 SPARQ_FLAG_NO_REALLOC, SPARQ_FLAG_GQA_SHARED, SPARQ_FLAG_RAGGED_BATCH = 1, 2, 4
+SPARQ_FLAG_TAU_SQRT_DH, SPARQ_FLAG_TAU_SQRT_R = 8, 16
 SPARQ_ERR_APPEND_FULL, SPARQ_ERR_EMPTY_SEQ, SPARQ_ERR_IDX_TRUNCATED, SPARQ_ERR_BAD_SEQ_LEN = 1, 2, 4, 8
 SPARQ_OK, SPARQ_EINVAL, SPARQ_EUNSUPPORTED, SPARQ_EWORKSPACE, SPARQ_ELAUNCH = 0, -1, -2, -3, -4
 
@@ -27,7 +28,8 @@ EXPORTS = ["sparq_workspace_bytes", "sparq_workspace_init", "sparq_kv_append", "
 class SparqShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("H_kv", ctypes.c_int32),
                 ("S_max", ctypes.c_int32), ("d_h", ctypes.c_int32), ("r", ctypes.c_int32),
-                ("k", ctypes.c_int32), ("dtype", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+                ("k", ctypes.c_int32), ("dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
+                ("local_window", ctypes.c_int32)]
 
 
 class SparqCache(ctypes.Structure):
@@ -99,9 +101,9 @@ def _stream(stream) -> int:
     return s.cuda_stream
 
 
-def make_shape(B, H, H_kv, S_max, d_h, r, k, dtype, flags=0) -> SparqShape:
+def make_shape(B, H, H_kv, S_max, d_h, r, k, dtype, flags=0, local_window=0) -> SparqShape:
     code = {torch.float16: SPARQ_F16, torch.bfloat16: SPARQ_BF16}.get(dtype, dtype)
-    return SparqShape(B, H, H_kv, S_max, d_h, r, k, int(code), flags)
+    return SparqShape(B, H, H_kv, S_max, d_h, r, k, int(code), flags, local_window)
 
 
 def make_cache(K, Kt, V, v_mean, seq_lens) -> SparqCache:

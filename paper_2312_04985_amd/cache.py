@@ -33,10 +33,10 @@ class DecodeCache:
         self._v_mean_alt = None      # second (v_mean, seq_lens) pair for the one-launch step, made on first use
         self._seq_lens_alt = None
 
-    def with_params(self, r: int, k: int, flags: int = 0):
-        """The same buffers seen through another (r, k, flags) setting."""
+    def with_params(self, r: int, k: int, flags: int = 0, local_window: int = 0):
+        """The same buffers seen through another (r, k, flags, local window) setting."""
         self.r, self.k = r, k
-        self.shape = B.make_shape(self.B, self.H, self.H_kv, self.S_max, self.d_h, r, k, self.dtype, flags)
+        self.shape = B.make_shape(self.B, self.H, self.H_kv, self.S_max, self.d_h, r, k, self.dtype, flags, local_window)
         return self
 
     def append(self, k_new: torch.Tensor, v_new: torch.Tensor, n_new_per_seq: Optional[torch.Tensor] = None, stream=None):

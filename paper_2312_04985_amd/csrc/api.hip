@@ -20,7 +20,10 @@ int check_shape(const sparq_shape* s) {
   if (s->r < 1 || s->r > s->d_h || s->k < 1) return SPARQ_EINVAL;
   if (s->dtype != SPARQ_F16 && s->dtype != SPARQ_BF16) return SPARQ_EINVAL;
   if (s->S_max % 64 != 0) return SPARQ_EINVAL;
-  if (s->flags & ~(uint32_t)(SPARQ_FLAG_NO_REALLOC | SPARQ_FLAG_GQA_SHARED | SPARQ_FLAG_RAGGED_BATCH)) return SPARQ_EINVAL;
+  if (s->flags & ~(uint32_t)(SPARQ_FLAG_NO_REALLOC | SPARQ_FLAG_GQA_SHARED | SPARQ_FLAG_RAGGED_BATCH |
+                             SPARQ_FLAG_TAU_SQRT_DH | SPARQ_FLAG_TAU_SQRT_R)) return SPARQ_EINVAL;
+  if ((s->flags & SPARQ_FLAG_TAU_SQRT_DH) && (s->flags & SPARQ_FLAG_TAU_SQRT_R)) return SPARQ_EINVAL;
+  if (s->local_window < 0) return SPARQ_EINVAL;
   if (s->d_h != 64 && s->d_h != 128 && s->d_h != 256) return SPARQ_EUNSUPPORTED;
   // element offsets inside one tensor are formed in size_t; the counts themselves stay in int32
   if ((int64_t)s->B * s->H > (int64_t)1 << 30) return SPARQ_EUNSUPPORTED;
@@ -214,6 +217,7 @@ int sparq_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
   a.chan_out = chan_out; a.err = static_cast<int32_t*>(workspace);
   a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h;
   a.r = shape->r; a.k = shape->k; a.idx_stride = idx_out ? idx_stride : 0; a.flags = shape->flags;
+  a.local_window = shape->local_window;
   return enqueue_decode(shape, a, workspace, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
@@ -240,6 +244,7 @@ int sparq_decode_step(const sparq_shape* shape, const sparq_cache* cache, const 
   a.chan_out = chan_out; a.err = static_cast<int32_t*>(workspace);
   a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h;
   a.r = shape->r; a.k = shape->k; a.idx_stride = idx_out ? idx_stride : 0; a.flags = shape->flags;
+  a.local_window = shape->local_window;
   return enqueue_decode(shape, a, workspace, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 

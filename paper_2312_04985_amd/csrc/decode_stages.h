@@ -110,6 +110,27 @@ __device__ __forceinline__ float select_channels(const QueryLds& Q, uint16_t qco
   return tau;
 }
 
+// The temperature actually used: Eq. (7), or one of the two fixed values of the ablation in Section 5.3
+// (flag bits 3 and 4).
+__device__ __forceinline__ float apply_tau_mode(float tau_l1, uint32_t flags, int d_h, int r) {
+  if (flags & 8u) return sqrtf((float)d_h);
+  if (flags & 16u) return sqrtf((float)r);
+  return tau_l1;
+}
+
+// Local window: the last n_local = min(l, kq) positions are selected unconditionally; the select then
+// runs over the S - n_local older positions for kq - n_local of them.
+struct Window {
+  int n_local, S_old, k_old;
+};
+__device__ __forceinline__ Window make_window(int local_window, int S, int kq) {
+  Window w;
+  w.n_local = local_window < kq ? local_window : kq;
+  w.S_old = S - w.n_local;
+  w.k_old = kq - w.n_local;
+  return w;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Step 1b: approximate logit numerators over the r selected rows of the S-contiguous key copy
 
@@ -188,9 +209,11 @@ struct SelectLds {
 // buffer is cleared; one wave finds the threshold digit, everyone picks it up after a barrier; the loop
 // ends as soon as the remaining bin is taken whole.  On return the selected keys are those with
 // (key & pmask) > pval plus the first `need` keys (by position) with (key & pmask) == pval.
+// kq = 0 (everything comes from the local window) selects nothing: returns a predicate no key meets.
 __device__ __forceinline__ void radix_select(const uint32_t* keys, int S, int kq, const SelectLds& sl,
                                              int tid, int lane, int wave, uint32_t& pmask, uint32_t& pval, int& need) {
   const int n_chunks = (S + 7) >> 3;
+  if (kq == 0) { pmask = 0xffffffffu; pval = 0xffffffffu; need = 0; return; }
   pmask = 0u; pval = 0u; need = kq;
   for (int pass = 0; pass < 3; ++pass) {
     const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
@@ -246,10 +269,13 @@ __device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wsum, 
 // beyond the position it records and all reads of a sweep precede its writes (the scan's barrier).
 // Ends with a barrier that also publishes the list.  esc = log2(e) / tau.  With WITH_ALPHA = false only
 // the list is produced (the grouped-query kernel gets alpha per query head elsewhere) and 0 is returned.
+// Positions >= forced_from (the local window) are taken whatever their keys; the predicate applies to
+// the positions before them.
 template <bool WITH_ALPHA = true>
-__device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t* list, int S, uint32_t pmask,
-                                                  uint32_t pval, int need, float dmax, float esc, int32_t* idx_out,
-                                                  int idx_stride, const SelectLds& sl, int tid, int lane, int wave) {
+__device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t* list, int S, int forced_from,
+                                                  uint32_t pmask, uint32_t pval, int need, float dmax, float esc,
+                                                  int32_t* idx_out, int idx_stride, const SelectLds& sl, int tid,
+                                                  int lane, int wave) {
   const int n_chunks = (S + 7) >> 3;
   float zsum = 0.0f, asum = 0.0f;
   uint32_t run_gt = 0, run_eq = 0;
@@ -270,8 +296,9 @@ __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const bool valid = (c * 8 + e) < S && c < n_chunks;
+      const bool old = (c * 8 + e) < forced_from;
       const uint32_t hi_bits = kx[e] & pmask;
-      const bool g = valid && hi_bits > pval, q = valid && hi_bits == pval;
+      const bool g = valid && (hi_bits > pval || !old), q = valid && old && hi_bits == pval;
       gt_bits |= (uint32_t)g << e; eq_bits |= (uint32_t)q << e;
       n_gt += g; n_eq += q;
     }

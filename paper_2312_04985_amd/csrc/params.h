@@ -23,6 +23,7 @@ struct DecodeArgs {
   void* out; float* alpha_out; int32_t* idx_out; int32_t* chan_out; int32_t* err;
   int32_t B, H, H_kv, S_max, d_h, r, k, idx_stride;
   uint32_t flags;
+  int32_t local_window;
 };
 
 struct AppendArgs {

@@ -116,7 +116,8 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   // ---------------- stage 0 ----------------
   for (int i = tid; i < 2 * kRadixBins; i += NT) L.sel.hist[i] = 0u;
   if (APPEND && tid < DH) { L.knew[tid] = kcode; L.vnew[tid] = vcode; }
-  const float tau = select_channels<T, DH>(L.qry, qcode, a.r, tid, lane, wave);
+  const float tau = apply_tau_mode(select_channels<T, DH>(L.qry, qcode, a.r, tid, lane, wave), a.flags, DH, a.r);
+  const Window win = make_window(a.local_window, S, kq);
   if (a.chan_out && tid < a.r) a.chan_out[(size_t)u * a.r + tid] = L.qry.chan[tid];
   float dot_new = 0.0f;   // approximate logit numerator of the appended row (every wave computes it)
   if (APPEND && appended) {
@@ -139,7 +140,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
         const float val = (APPEND && appended && c * 8 + e == S - 1) ? dot_new : acc[e];
         tmax = fmaxf(tmax, val);
         kx[e] = float_to_key(val);
-        atomicAdd(&L.sel.hist[hist_slot(kx[e] >> 21)], 1u);
+        if (c * 8 + e < win.S_old) atomicAdd(&L.sel.hist[hist_slot(kx[e] >> 21)], 1u);
       } else {
         kx[e] = 0u;
       }
@@ -158,8 +159,8 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   // ---------------- stage 2 ----------------
   uint32_t pmask, pval;
   int need;
-  radix_select(L.keys, S, kq, L.sel, tid, lane, wave, pmask, pval, need);
-  const float alpha = compact_selected(L.keys, L.keys, S, pmask, pval, need, dmax, kLog2e / tau, idx_out, a.idx_stride,
+  radix_select(L.keys, win.S_old, win.k_old, L.sel, tid, lane, wave, pmask, pval, need);
+  const float alpha = compact_selected(L.keys, L.keys, S, win.S_old, pmask, pval, need, dmax, kLog2e / tau, idx_out, a.idx_stride,
                                        L.sel, tid, lane, wave);
   if (tid == 0) {
     if (a.alpha_out) a.alpha_out[u] = alpha;

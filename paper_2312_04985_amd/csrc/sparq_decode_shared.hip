@@ -222,12 +222,14 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
     for (int h = 0; h < G; ++h) {
       const float all = wave_sum(l1a[h]), part = wave_sum(l1s[h]);
       const float tau = part > 0.0f ? sqrtf((float)DH * part / all) : sqrtf((float)DH);   // all logits 0 then
-      esc[h] = kLog2e / tau;
+      esc[h] = kLog2e / apply_tau_mode(tau, a.flags, DH, a.r);
     }
   }
   __syncthreads();
   if (a.chan_out)
     for (int i = tid; i < G * a.r; i += NT) a.chan_out[u0 * a.r + i] = L.chan[i % a.r];
+
+  const Window win = make_window(a.local_window, S, kq);
 
   // ---------------- pass A: per-head max and sum-exp of the approximate logits ----------------
   const size_t row_bytes = (size_t)a.S_max * 2;
@@ -289,7 +291,7 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
 #pragma unroll
         for (int h = 0; h < G; ++h) score += exp2f((acc[h][e] - mh[h]) * esc[h]) * inv_z[h];
         kx[e] = float_to_key(score);
-        atomicAdd(&L.sel.hist[hist_slot(kx[e] >> 21)], 1u);
+        if (c * 8 + e < win.S_old) atomicAdd(&L.sel.hist[hist_slot(kx[e] >> 21)], 1u);
       } else {
         kx[e] = 0u;
       }
@@ -303,9 +305,9 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
   // ---------------- stage 2: the kq positions of largest group score ----------------
   uint32_t pmask, pval;
   int need;
-  radix_select(L.keys, S, kq, L.sel, tid, lane, wave, pmask, pval, need);
+  radix_select(L.keys, win.S_old, win.k_old, L.sel, tid, lane, wave, pmask, pval, need);
   int32_t* idx_out = a.idx_out ? a.idx_out + u0 * a.idx_stride : nullptr;
-  compact_selected<false>(L.keys, L.keys, S, pmask, pval, need, 0.0f, 0.0f, idx_out, a.idx_stride, L.sel, tid, lane, wave);
+  compact_selected<false>(L.keys, L.keys, S, win.S_old, pmask, pval, need, 0.0f, 0.0f, idx_out, a.idx_stride, L.sel, tid, lane, wave);
   if (idx_out) {
     if (tid == 0 && kq > a.idx_stride) atomicOr(a.err, 4);
     for (int n = kq + tid; n < a.idx_stride; n += NT) idx_out[n] = -1;

@@ -60,7 +60,7 @@ __global__ __launch_bounds__(NT, 4) void split_scores(const SplitArgs a) {
   }
 
   const QueryLds Q{mag, rankp, qf, qs, chan};
-  const float tau = select_channels<T, DH>(Q, qcode, d.r, tid, lane, wave);
+  const float tau = apply_tau_mode(select_channels<T, DH>(Q, qcode, d.r, tid, lane, wave), d.flags, DH, d.r);
   if (s == 0) {
     if (d.chan_out && tid < d.r) d.chan_out[(size_t)u * d.r + tid] = chan[tid];
     if (tid == 0) a.tau_ws[u] = tau;
@@ -119,6 +119,7 @@ __global__ __launch_bounds__(NT) void split_select(const SplitArgs a) {
   if (kb < 1) kb = 1;
   const int kq = kb < S ? kb : S;
   int32_t* idx_out = d.idx_out ? d.idx_out + (size_t)u * d.idx_stride : nullptr;
+  const Window win = make_window(d.local_window, S, kq);
 
   for (int i = tid; i < 2 * kRadixBins; i += NT) hist[i] = 0u;
   float dmax = -INFINITY;
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(NT) void split_select(const SplitArgs a) {
         const uint32_t kx[8] = {lo[t].x, lo[t].y, lo[t].z, lo[t].w, hi[t].x, hi[t].y, hi[t].z, hi[t].w};
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-          if (c * 8 + e < S) atomicAdd(&hist[hist_slot(kx[e] >> 21)], 1u);
+          if (c * 8 + e < win.S_old) atomicAdd(&hist[hist_slot(kx[e] >> 21)], 1u);
       }
     }
   }
@@ -155,9 +156,9 @@ __global__ __launch_bounds__(NT) void split_select(const SplitArgs a) {
   const SelectLds sel{hist, wcnt, ctl, red};
   uint32_t pmask, pval;
   int need;
-  radix_select(keys, S, kq, sel, tid, lane, wave, pmask, pval, need);
+  radix_select(keys, win.S_old, win.k_old, sel, tid, lane, wave, pmask, pval, need);
   uint32_t* list = reinterpret_cast<uint32_t*>(a.list_ws + (size_t)u * d.S_max);
-  const float alpha = compact_selected(keys, list, S, pmask, pval, need, dmax, kLog2e / tau, idx_out, d.idx_stride,
+  const float alpha = compact_selected(keys, list, S, win.S_old, pmask, pval, need, dmax, kLog2e / tau, idx_out, d.idx_stride,
                                        sel, tid, lane, wave);
   if (tid == 0) {
     a.alpha_ws[u] = alpha;

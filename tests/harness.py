@@ -96,19 +96,23 @@ def check_cache_state(b: Built):
     return Kh, Vh
 
 
-def check_positions(gpu_idx: np.ndarray, ref: O.SparqResult, Kf: np.ndarray, qf: np.ndarray, seq, kps, w) -> dict:
+def check_positions(gpu_idx: np.ndarray, ref: O.SparqResult, Kf: np.ndarray, qf: np.ndarray, seq, kps, w,
+                    local_window: int = 0) -> dict:
     """Index-set parity.  The GPU list must hold min(k_b, S_b) distinct valid positions in ascending
     order, padded with -1.  It must contain every position the oracle ranks clearly inside the top-k
     and none it ranks clearly outside, under two notions of 'clearly':
       A  the approximate score s-hat differs from the threshold score by more than 1e-6;
       B  the approximate dot product differs from the threshold by more than twice the worst-case
          fp32 rounding of an r-term FMA chain (r * 2^-24 * sum_j |q_j K_ij|).
+    With a local window the last min(l, k_b) positions must be present and the ranking concerns the
+    older positions only.
     Returns counts (units, units whose set equals the oracle's exactly, positions left uncompared)."""
     Bn, H = gpu_idx.shape[:2]
     g = w.H // w.H_kv
     exact = 0; skipped_a = 0; skipped_b = 0
     for b in range(Bn):
         S = int(seq[b]); kq = min(int(kps[b]) if kps is not None else w.k, S)
+        n_local = min(local_window, kq); S_old = S - n_local; k_old = kq - n_local
         for h in range(H):
             got = gpu_idx[b, h]
             assert (got[kq:] == -1).all(), "padding"
@@ -118,29 +122,32 @@ def check_positions(gpu_idx: np.ndarray, ref: O.SparqResult, Kf: np.ndarray, qf:
             if np.array_equal(sel, want):
                 exact += 1
                 continue
-            assert kq < S
-            z = ref.z[b, h, :S]; tau = ref.tau[b, h]
+            assert sel[k_old:].tolist() == list(range(S_old, S)), "local window"
+            assert 0 < k_old < S_old
+            z_all = ref.z[b, h, :S]; tau = ref.tau[b, h]
+            z = z_all[:S_old]
             order = np.sort(z)[::-1]
-            z_in, z_out = order[kq - 1], order[kq]
-            got_mask = np.zeros(S, dtype=bool); got_mask[sel] = True
+            z_in, z_out = order[k_old - 1], order[k_old]
+            got_mask = np.zeros(S_old, dtype=bool); got_mask[sel[:k_old]] = True
             # A: s-hat gap
-            m = z.max(); e = np.exp(z - m); shat = e / e.sum()
-            s_in, s_out = math.exp(z_in - m) / e.sum(), math.exp(z_out - m) / e.sum()
+            m = z_all.max(); total = np.exp(z_all - m).sum(); shat = np.exp(z - m) / total
+            s_in, s_out = math.exp(z_in - m) / total, math.exp(z_out - m) / total
             sure_in = shat - s_out > SHAT_GAP; sure_out = s_in - shat > SHAT_GAP
             assert got_mask[sure_in].all() and not got_mask[sure_out].any(), f"score-gap check failed at unit ({b},{h})"
-            skipped_a += int(S - sure_in.sum() - sure_out.sum())
+            skipped_a += int(S_old - sure_in.sum() - sure_out.sum())
             # B: rigorous fp32 bound in dot-product space
             i1 = ref.i1[b, h]
-            absdot = np.abs(Kf[b, h // g, :S][:, i1] * qf[b, h, i1][None, :]).sum(axis=1)
+            absdot = np.abs(Kf[b, h // g, :S_old][:, i1] * qf[b, h, i1][None, :]).sum(axis=1)
             E = 1.01 * w.r * 2.0 ** -24 * absdot.max()
             d = z * tau
             sure_in = d - z_out * tau > 2 * E; sure_out = z_in * tau - d > 2 * E
             assert got_mask[sure_in].all() and not got_mask[sure_out].any(), f"fp32-bound check failed at unit ({b},{h})"
-            skipped_b += int(S - sure_in.sum() - sure_out.sum())
+            skipped_b += int(S_old - sure_in.sum() - sure_out.sum())
     return dict(units=Bn * H, exact_sets=exact, uncompared_score_gap=skipped_a, uncompared_fp32_bound=skipped_b)
 
 
-def check_positions_shared(gpu_idx: np.ndarray, ref: O.SparqResult, Kf: np.ndarray, qf: np.ndarray, seq, kps, w) -> dict:
+def check_positions_shared(gpu_idx: np.ndarray, ref: O.SparqResult, Kf: np.ndarray, qf: np.ndarray, seq, kps, w,
+                           local_window: int = 0) -> dict:
     """Index-set parity under the grouped-query rule: all heads of a group report the same list; the
     list is the top-k of the group score sum_h s-hat_h.  Positions whose oracle score is within
     1e-6 + 2 * (2 E + 3e-6) * score of the threshold score are not compared, E being the worst-case
@@ -151,6 +158,7 @@ def check_positions_shared(gpu_idx: np.ndarray, ref: O.SparqResult, Kf: np.ndarr
     exact = 0; skipped = 0; E_max = 0.0
     for b in range(Bn):
         S = int(seq[b]); kq = min(int(kps[b]) if kps is not None else w.k, S)
+        n_local = min(local_window, kq); S_old = S - n_local; k_old = kq - n_local
         for hk in range(w.H_kv):
             heads = range(hk * g, (hk + 1) * g)
             got = gpu_idx[b, hk * g]
@@ -170,25 +178,27 @@ def check_positions_shared(gpu_idx: np.ndarray, ref: O.SparqResult, Kf: np.ndarr
             if np.array_equal(sel, ref.i2[b, hk * g, :kq]):
                 exact += 1
                 continue
-            assert kq < S
+            assert sel[k_old:].tolist() == list(range(S_old, S)), "local window"
+            assert 0 < k_old < S_old
+            score = score[:S_old]
             order = np.sort(score)[::-1]
-            s_in, s_out = order[kq - 1], order[kq]
+            s_in, s_out = order[k_old - 1], order[k_old]
             rel = 2 * (2 * E + 3e-6)
-            got_mask = np.zeros(S, dtype=bool); got_mask[sel] = True
+            got_mask = np.zeros(S_old, dtype=bool); got_mask[sel[:k_old]] = True
             sure_in = score - s_out > 1e-6 + rel * np.maximum(score, s_out)
             sure_out = s_in - score > 1e-6 + rel * np.maximum(score, s_in)
             assert got_mask[sure_in].all() and not got_mask[sure_out].any(), f"group-score check failed at ({b},{hk})"
-            skipped += int(S - sure_in.sum() - sure_out.sum())
+            skipped += int(S_old - sure_in.sum() - sure_out.sum())
     return dict(units=Bn * w.H_kv, exact_sets=exact, uncompared_score_gap=skipped, uncompared_fp32_bound=skipped,
                 logit_err_bound=E_max)
 
 
-def compare_decode(b: Built, q: torch.Tensor, *, flags: int = 0, check_state: bool = True) -> dict:
+def compare_decode(b: Built, q: torch.Tensor, *, flags: int = 0, check_state: bool = True, local_window: int = 0) -> dict:
     """Run sparq_decode and dense_decode on the GPU and the oracle on the host; assert parity."""
     w, c = b.w, b.cache
     dev_k = None if b.k_per_seq is None else b.k_per_seq.to(c.device)
     kq_max = int(torch.minimum(b.k_per_seq if b.k_per_seq is not None else torch.full_like(b.seq_lens, w.k), b.seq_lens).max())
-    c.with_params(w.r, w.k, flags)
+    c.with_params(w.r, w.k, flags, local_window)
     out, alpha, idx, chan = c.decode(q, dev_k, aux=True, idx_stride=max(kq_max, 1))
     out2 = c.decode(q, dev_k)                       # no optional outputs: same kernel, must be bit-identical
     dense = c.dense(q)
@@ -202,17 +212,19 @@ def compare_decode(b: Built, q: torch.Tensor, *, flags: int = 0, check_state: bo
         Kh, Vh = host_cache_codes(b, c.S_max)
     qh = W.to_codes(q)
     seq = b.seq_lens.numpy(); kps = None if b.k_per_seq is None else b.k_per_seq.numpy()
-    ref = O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags & 3, k_per_seq=kps, want_z=True)
+    oflags = flags & ~4          # bit 2 is a scheduling hint of the library
+    ref = O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=oflags, k_per_seq=kps, want_z=True,
+                         local_window=local_window)
     Kf = O.to_double(Kh, w.dtype_code); qf = O.to_double(qh, w.dtype_code)
 
     assert np.array_equal(chan.cpu().numpy(), ref.i1), "i1 (top-r channels) must match exactly"
     gi = idx.cpu().numpy()
     shared = bool(flags & 2) and w.H != w.H_kv
-    stats = (check_positions_shared if shared else check_positions)(gi, ref, Kf, qf, seq, kps, w)
+    stats = (check_positions_shared if shared else check_positions)(gi, ref, Kf, qf, seq, kps, w, local_window)
     # outputs are compared with the oracle run on the GPU's own position sets, so that a position
     # inside the uncompared band cannot pass for, or hide, an output error
     ref_g = ref if stats["exact_sets"] == stats["units"] else \
-        O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags & 3, k_per_seq=kps, given_i2=gi)
+        O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=oflags, k_per_seq=kps, given_i2=gi)
     a_err = np.abs(alpha.cpu().numpy().astype(np.float64) - ref_g.alpha).max()
     # The grouped-query kernel does not keep G x S logits: alpha's numerator comes from logits
     # recomputed on the gathered key rows, the normaliser from the streamed ones.  The two fp32
@@ -276,7 +288,7 @@ def compare_sampled(b: Built, q: torch.Tensor, *, n_units: int = 48, flags: int 
     got_vm = np.stack([c.v_mean[divmod(int(p), w.H_kv)].cpu().numpy() for p in picks]).astype(np.float64)
     assert np.abs(got_vm - vbar).max() <= VMEAN_TOL, "v_mean"
 
-    ref = O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags & 3, k_per_seq=kps, want_z=True)
+    ref = O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags & ~4, k_per_seq=kps, want_z=True)
     Kf = O.to_double(Kh, w.dtype_code); qf = O.to_double(qh, w.dtype_code)
     assert np.array_equal(g_chan, ref.i1), "i1 (top-r channels) must match exactly"
     stride = ref.i2.shape[-1]
@@ -284,7 +296,7 @@ def compare_sampled(b: Built, q: torch.Tensor, *, n_units: int = 48, flags: int 
     ws = W.scaled(w, B=n, H=g, H_kv=1)
     stats = check_positions(g_idx[:, :, :stride], ref, Kf, qf, seq, kps, ws)
     ref_g = ref if stats["exact_sets"] == stats["units"] else \
-        O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags & 3, k_per_seq=kps,
+        O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=flags & ~4, k_per_seq=kps,
                        given_i2=np.ascontiguousarray(g_idx[:, :, :stride]))
     a_err = np.abs(g_alpha - ref_g.alpha).max()
     assert a_err <= ALPHA_TOL, f"alpha error {a_err}"

@@ -32,7 +32,7 @@ def test_status_strings():
 
 
 def shape(**kw):
-    d = dict(B=2, H=4, H_kv=2, S_max=128, d_h=128, r=16, k=8, dtype=0, flags=0)
+    d = dict(B=2, H=4, H_kv=2, S_max=128, d_h=128, r=16, k=8, dtype=0, flags=0, local_window=0)
     d.update(kw)
     return B.SparqShape(*[d[f] for f, _ in B.SparqShape._fields_])
 
@@ -43,7 +43,8 @@ def test_workspace_bytes_and_shape_validation():
     assert B.sparq_workspace_bytes(shape(S_max=32768, B=1, H=32, H_kv=8)) > need
     for bad, code in [(dict(S_max=100), B.SPARQ_EINVAL), (dict(H=5), B.SPARQ_EINVAL), (dict(r=0), B.SPARQ_EINVAL),
                       (dict(r=129), B.SPARQ_EINVAL), (dict(k=0), B.SPARQ_EINVAL), (dict(dtype=2), B.SPARQ_EINVAL),
-                      (dict(flags=64), B.SPARQ_EINVAL), (dict(B=0), B.SPARQ_EINVAL), (dict(d_h=80, r=16), B.SPARQ_EUNSUPPORTED)]:
+                      (dict(flags=64), B.SPARQ_EINVAL), (dict(flags=8 | 16), B.SPARQ_EINVAL), (dict(local_window=-1), B.SPARQ_EINVAL),
+                      (dict(B=0), B.SPARQ_EINVAL), (dict(d_h=80, r=16), B.SPARQ_EUNSUPPORTED)]:
         with pytest.raises(B.SparqError) as e:
             B.sparq_workspace_bytes(shape(**bad))
         assert e.value.status == code, bad

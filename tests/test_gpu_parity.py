@@ -25,14 +25,14 @@ def say(*a):
     sys.stdout.flush()
 
 
-def run(w, *, n_q=1, q_scale=1.0, tie_channels=0, flags=0, **build_kw):
+def run(w, *, n_q=1, q_scale=1.0, tie_channels=0, flags=0, local_window=0, **build_kw):
     say(f"[case] {w.name} B={w.B} H={w.H}/{w.H_kv} d_h={w.d_h} S={w.S} r={w.r} k={w.k} {w.dtype} "
-        f"ragged={w.ragged} q_scale={q_scale} flags={flags} {build_kw}")
+        f"ragged={w.ragged} q_scale={q_scale} flags={flags} l={local_window} {build_kw}")
     b = Hn.build_cache(w, **build_kw)
     q = W.draw_queries(w, b.K_src, b.seq_lens, n=n_q, q_scale=q_scale, tie_channels=tie_channels)
     stats = None
     for i in range(n_q):
-        stats = Hn.compare_decode(b, q[i], flags=flags, check_state=(i == 0))
+        stats = Hn.compare_decode(b, q[i], flags=flags, check_state=(i == 0), local_window=local_window)
         say("   ", stats)
     return stats
 
@@ -340,3 +340,46 @@ def test_split_plan_ragged_short_and_empty_sequences():
                        b.V_src[keep].contiguous(), seq[keep], None)
         sub.cache.append(sub.K_src, sub.V_src, seq[keep].cuda())
         say(Hn.compare_decode(sub, q[0][keep].contiguous()))
+
+
+# ------------------------------------------------------------------ ablation switches
+
+@pytest.mark.parametrize("flag", [B.SPARQ_FLAG_TAU_SQRT_DH, B.SPARQ_FLAG_TAU_SQRT_R])
+def test_fixed_temperatures(flag):
+    """Section 5.3 'Approximate softmax temperature': tau = sqrt(d_h) and tau = sqrt(r)."""
+    w = W.Workload("tau_modes", 2, 4, 4, 128, 1500, 16, 128, "f16", seed=60)
+    st = run(w, flags=flag, q_scale=0.02, v_offset=True)
+    assert 0.02 < st["alpha_min"] < 0.9          # the blend term is exercised
+    wg = W.Workload("tau_modes_gqa", 2, 8, 2, 128, 1100, 16, 96, "bf16", seed=61)
+    run(wg, flags=flag, q_scale=0.02, v_offset=True)                                  # independent heads
+    run(wg, flags=flag | B.SPARQ_FLAG_GQA_SHARED, q_scale=0.02, v_offset=True)        # the paper's group rule
+    ws = W.Workload("tau_modes_split", 1, 4, 4, 128, 9000, 32, 300, "f16", seed=62)   # split-sequence plan
+    run(ws, flags=flag, q_scale=0.01, v_offset=True)
+
+
+@pytest.mark.parametrize("l", [1, 16, 64, 200])
+def test_local_window(l):
+    """Experimental-setup table, 'Local window l': the l most recent positions always selected."""
+    w = W.Workload("window", 2, 4, 4, 128, 1500, 16, 64, "f16", seed=63)
+    seq = torch.tensor([1500, 61], dtype=torch.int32)         # the second sequence is shorter than k
+    st = run(w, local_window=l, q_scale=0.02, v_offset=True, seq_lens=seq)
+    wg = W.Workload("window_gqa", 1, 8, 2, 128, 1100, 16, 64, "bf16", seed=64)
+    run(wg, local_window=l, flags=B.SPARQ_FLAG_GQA_SHARED, q_scale=0.02, v_offset=True)
+    ws = W.Workload("window_split", 1, 4, 4, 128, 9000, 32, 64, "f16", seed=65)
+    run(ws, local_window=l, q_scale=0.01, v_offset=True)
+
+
+def test_local_window_with_the_one_call_step():
+    """The appended row is inside any window l >= 1: it must be taken from the inputs, not read back."""
+    w = W.Workload("window_step", 2, 4, 2, 128, 700, 16, 32, "f16", seed=66)
+    b = Hn.build_cache(w, v_offset=True)
+    b.cache.with_params(w.r, w.k, 0, 8)
+    kn, vn = W.draw_kv(W.scaled(w, seed=80), "cuda", n_rows=1, v_offset=True)
+    q = W.draw_queries(w, b.K_src, b.seq_lens, q_scale=0.02)[0]
+    out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q)
+    torch.cuda.synchronize()
+    grown = Hn.Built(w, b.cache, torch.cat([b.K_src, kn], dim=2), torch.cat([b.V_src, vn], dim=2), b.seq_lens + 1, None)
+    say(Hn.compare_decode(grown, q, local_window=8))
+    b.cache.with_params(w.r, w.k, 0, 8)
+    again = b.cache.decode(q)
+    assert (out.float() - again.float()).abs().max().item() <= 2e-3
