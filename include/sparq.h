@@ -59,7 +59,11 @@ enum {
   /* the fixed temperatures of the paper's ablation (Section 5.3, "Approximate softmax
    * temperature") in place of Eq. (7): tau = sqrt(d_h), or tau = sqrt(r).  At most one of the two. */
   SPARQ_FLAG_TAU_SQRT_DH = 1u << 3,
-  SPARQ_FLAG_TAU_SQRT_R = 1u << 4
+  SPARQ_FLAG_TAU_SQRT_R = 1u << 4,
+  /* the key cache is stored once, d_h-contiguous only (the "1 x K" variant of Section 6.1): cache.Kt
+   * is ignored and may be null, sparq_kv_append writes no second copy, and Step 1 reads the rows of K
+   * whole (S d_h elements instead of S r).  Not combined with SPARQ_FLAG_GQA_SHARED. */
+  SPARQ_FLAG_SINGLE_K = 1u << 5
 };
 
 /* bits of the device-side error word (sparq_async_error) */

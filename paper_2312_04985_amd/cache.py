@@ -23,7 +23,8 @@ class DecodeCache:
         self.shape = B.make_shape(Bsz, H, H_kv, S_max, d_h, r, k, dtype, flags)
         mk = torch.zeros if poison is None else (lambda *a, **kw: torch.full(*a, fill_value=poison, **kw))
         self.K = mk((Bsz, H_kv, S_max, d_h), dtype=dtype, device=self.device)
-        self.Kt = mk((Bsz, H_kv, d_h, S_max), dtype=dtype, device=self.device)
+        # with SPARQ_FLAG_SINGLE_K at construction there is no second key copy at all
+        self.Kt = None if flags & B.SPARQ_FLAG_SINGLE_K else mk((Bsz, H_kv, d_h, S_max), dtype=dtype, device=self.device)
         self.V = mk((Bsz, H_kv, S_max, d_h), dtype=dtype, device=self.device)
         self.v_mean = torch.zeros((Bsz, H_kv, d_h), dtype=torch.float32, device=self.device)
         self.seq_lens = torch.zeros((Bsz,), dtype=torch.int32, device=self.device)

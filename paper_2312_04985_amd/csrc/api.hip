@@ -21,7 +21,7 @@ int check_shape(const sparq_shape* s) {
   if (s->dtype != SPARQ_F16 && s->dtype != SPARQ_BF16) return SPARQ_EINVAL;
   if (s->S_max % 64 != 0) return SPARQ_EINVAL;
   if (s->flags & ~(uint32_t)(SPARQ_FLAG_NO_REALLOC | SPARQ_FLAG_GQA_SHARED | SPARQ_FLAG_RAGGED_BATCH |
-                             SPARQ_FLAG_TAU_SQRT_DH | SPARQ_FLAG_TAU_SQRT_R)) return SPARQ_EINVAL;
+                             SPARQ_FLAG_TAU_SQRT_DH | SPARQ_FLAG_TAU_SQRT_R | SPARQ_FLAG_SINGLE_K)) return SPARQ_EINVAL;
   if ((s->flags & SPARQ_FLAG_TAU_SQRT_DH) && (s->flags & SPARQ_FLAG_TAU_SQRT_R)) return SPARQ_EINVAL;
   if (s->local_window < 0) return SPARQ_EINVAL;
   if (s->d_h != 64 && s->d_h != 128 && s->d_h != 256) return SPARQ_EUNSUPPORTED;
@@ -30,9 +30,10 @@ int check_shape(const sparq_shape* s) {
   return SPARQ_OK;
 }
 
-int check_cache(const sparq_cache* c) {
-  if (!c || !c->K || !c->Kt || !c->V || !c->v_mean || !c->seq_lens) return SPARQ_EINVAL;
-  if (!aligned16(c->K) || !aligned16(c->Kt) || !aligned16(c->V) || !aligned16(c->v_mean)) return SPARQ_EINVAL;
+int check_cache(const sparq_cache* c, const sparq_shape* s) {
+  if (!c || !c->K || !c->V || !c->v_mean || !c->seq_lens) return SPARQ_EINVAL;
+  if (!aligned16(c->K) || !aligned16(c->V) || !aligned16(c->v_mean)) return SPARQ_EINVAL;
+  if (!(s->flags & SPARQ_FLAG_SINGLE_K) && (!c->Kt || !aligned16(c->Kt))) return SPARQ_EINVAL;
   return SPARQ_OK;
 }
 
@@ -117,18 +118,20 @@ bool wants_shared(const sparq_shape* shape) {
   return (shape->flags & SPARQ_FLAG_GQA_SHARED) && shape->H != shape->H_kv;
 }
 
+bool single_k(const sparq_shape* shape) { return (shape->flags & SPARQ_FLAG_SINGLE_K) != 0; }
+
 // enqueue one decode over `a` with the plan the shape calls for
 hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* workspace, hipStream_t s) {
   int n_split = 0;
-  const bool shared = wants_shared(shape);
-  const bool split = !shared && split_plan(shape, &n_split);
-  if (!shared && !split) return launch_decode(a, shape->dtype, s);
+  const bool shared = wants_shared(shape), one_k = single_k(shape);
+  const bool split = !shared && !one_k && split_plan(shape, &n_split);
+  if (!shared && !split && !one_k) return launch_decode(a, shape->dtype, s);
   DecodeArgs d = a;
   if (a.k_new) {
     // only the one-workgroup-per-head kernel has the append built in: append into the *_next state
     // with the append kernel, then decode from that state
     AppendArgs ap;
-    ap.K = a.K; ap.Kt = a.Kt; ap.V = a.V; ap.v_mean = const_cast<float*>(a.v_mean); ap.seq_lens = const_cast<int32_t*>(a.seq_lens);
+    ap.K = a.K; ap.Kt = one_k ? nullptr : a.Kt; ap.V = a.V; ap.v_mean = const_cast<float*>(a.v_mean); ap.seq_lens = const_cast<int32_t*>(a.seq_lens);
     ap.v_mean_out = a.v_mean_next; ap.seq_lens_out = a.seq_lens_next;
     ap.k_new = a.k_new; ap.v_new = a.v_new; ap.n_new_per_seq = nullptr; ap.err = a.err;
     ap.B = a.B; ap.H_kv = a.H_kv; ap.S_max = a.S_max; ap.d_h = a.d_h; ap.n_new = 1;
@@ -137,6 +140,7 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
     d.v_mean = a.v_mean_next; d.seq_lens = a.seq_lens_next;
     d.k_new = nullptr; d.v_new = nullptr; d.v_mean_next = nullptr; d.seq_lens_next = nullptr;
   }
+  if (one_k) return launch_decode_single_k(d, shape->dtype, s);
   if (shared) return launch_decode_shared(d, shape->dtype, s);
   const SplitLayout l = split_layout(shape, n_split);
   char* w = static_cast<char*>(workspace);
@@ -156,6 +160,11 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
 bool decode_supported(const sparq_shape* shape) {
   int n_split;
   const size_t lds_max = (size_t)max_lds_bytes();
+  if (single_k(shape)) {
+    if (wants_shared(shape)) return false;
+    const size_t need = decode_single_k_lds_bytes(shape->S_max, shape->d_h);
+    return need != 0 && need <= lds_max;
+  }
   if (wants_shared(shape)) {
     const size_t need = decode_shared_lds_bytes(shape->S_max, shape->d_h, shape->H / shape->H_kv);
     return need != 0 && need <= lds_max;
@@ -185,13 +194,13 @@ int sparq_kv_append(const sparq_shape* shape, const sparq_cache* cache, const vo
                     const void* v_new, int32_t n_new, const int32_t* n_new_per_seq,
                     void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = check_shape(shape);
-  if (rc == SPARQ_OK) rc = check_cache(cache);
+  if (rc == SPARQ_OK) rc = check_cache(cache, shape);
   if (rc != SPARQ_OK) return rc;
   if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new) || n_new < 1 || n_new > shape->S_max) return SPARQ_EINVAL;
   rc = check_workspace(shape, workspace, workspace_bytes);
   if (rc != SPARQ_OK) return rc;
   AppendArgs a;
-  a.K = cache->K; a.Kt = cache->Kt; a.V = cache->V; a.v_mean = cache->v_mean; a.seq_lens = cache->seq_lens;
+  a.K = cache->K; a.Kt = single_k(shape) ? nullptr : cache->Kt; a.V = cache->V; a.v_mean = cache->v_mean; a.seq_lens = cache->seq_lens;
   a.v_mean_out = cache->v_mean; a.seq_lens_out = cache->seq_lens;
   a.k_new = k_new; a.v_new = v_new; a.n_new_per_seq = n_new_per_seq; a.err = static_cast<int32_t*>(workspace);
   a.B = shape->B; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h; a.n_new = n_new;
@@ -203,7 +212,7 @@ int sparq_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
                  int32_t idx_stride, int32_t* chan_out, void* workspace, size_t workspace_bytes,
                  void* hip_stream) {
   int rc = check_shape(shape);
-  if (rc == SPARQ_OK) rc = check_cache(cache);
+  if (rc == SPARQ_OK) rc = check_cache(cache, shape);
   if (rc != SPARQ_OK) return rc;
   if (!q || !out || !aligned16(q) || !aligned16(out)) return SPARQ_EINVAL;
   if (idx_out && idx_stride < 1) return SPARQ_EINVAL;
@@ -227,7 +236,7 @@ int sparq_decode_step(const sparq_shape* shape, const sparq_cache* cache, const 
                       int32_t idx_stride, int32_t* chan_out, void* workspace, size_t workspace_bytes,
                       void* hip_stream) {
   int rc = check_shape(shape);
-  if (rc == SPARQ_OK) rc = check_cache(cache);
+  if (rc == SPARQ_OK) rc = check_cache(cache, shape);
   if (rc != SPARQ_OK) return rc;
   if (!q || !out || !aligned16(q) || !aligned16(out)) return SPARQ_EINVAL;
   if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)) return SPARQ_EINVAL;
@@ -251,7 +260,7 @@ int sparq_decode_step(const sparq_shape* shape, const sparq_cache* cache, const 
 int dense_decode(const sparq_shape* shape, const sparq_cache* cache, const void* q, void* out,
                  void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = check_shape(shape);
-  if (rc == SPARQ_OK) rc = check_cache(cache);
+  if (rc == SPARQ_OK) rc = check_cache(cache, shape);
   if (rc != SPARQ_OK) return rc;
   if (!q || !out || !aligned16(q) || !aligned16(out)) return SPARQ_EINVAL;
   rc = check_workspace(shape, workspace, workspace_bytes);

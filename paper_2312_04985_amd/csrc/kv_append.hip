@@ -42,11 +42,13 @@ __global__ __launch_bounds__(512) void append_one_row(const AppendArgs a) {
     *reinterpret_cast<uint4*>(Krow) = kc;
     *reinterpret_cast<uint4*>(Vrow) = vc;
     // the same 8 key elements go down column S of the S-contiguous copy (2-byte stores)
-    uint16_t* Ktcol = reinterpret_cast<uint16_t*>(a.Kt) + (head * a.d_h + j0) * a.S_max + S;
-    const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w};
+    if (a.Kt) {   // null: the cache keeps K once
+      uint16_t* Ktcol = reinterpret_cast<uint16_t*>(a.Kt) + (head * a.d_h + j0) * a.S_max + S;
+      const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w};
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-      Ktcol[(size_t)e * a.S_max] = (uint16_t)((e & 1) ? (kw[e >> 1] >> 16) : (kw[e >> 1] & 0xffffu));
+      for (int e = 0; e < 8; ++e)
+        Ktcol[(size_t)e * a.S_max] = (uint16_t)((e & 1) ? (kw[e >> 1] >> 16) : (kw[e >> 1] & 0xffffu));
+    }
     // running mean: v_mean += (v - v_mean) / (S + 1)
     const float* vm = a.v_mean + head * a.d_h + j0;
     float* vo = a.v_mean_out + head * a.d_h + j0;
@@ -108,8 +110,9 @@ __global__ __launch_bounds__(BT) void append_rows(const AppendArgs a) {
       for (int e = 0; e < 8; ++e) sum[e] += (double)f[e];
     }
     __syncthreads();
-    for (int j = wave; j < DH; j += BT / 64)
-      if (lane < rows) Ktdst[(size_t)j * a.S_max + n0 + lane] = tile[lane * LD + j];
+    if (a.Kt)
+      for (int j = wave; j < DH; j += BT / 64)
+        if (lane < rows) Ktdst[(size_t)j * a.S_max + n0 + lane] = tile[lane * LD + j];
     __syncthreads();
   }
 #pragma unroll

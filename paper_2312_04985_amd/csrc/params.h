@@ -58,6 +58,8 @@ size_t split_select_lds_bytes(int S_max);
 size_t decode_shared_lds_bytes(int S_max, int d_h, int g);   // 0: no grouped-query kernel for this shape
 
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s);
+size_t decode_single_k_lds_bytes(int S_max, int d_h);
+hipError_t launch_decode_single_k(const DecodeArgs& a, int dtype, hipStream_t s);
 hipError_t launch_decode_shared(const DecodeArgs& a, int dtype, hipStream_t s);
 hipError_t launch_decode_split(const SplitArgs& a, int dtype, hipStream_t s);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t s);

@@ -45,14 +45,14 @@ class Built:
 
 def build_cache(w: W.Workload, *, S_max: Optional[int] = None, seq_lens: Optional[torch.Tensor] = None,
                 v_offset=False, dup_rows=0, single_appends: int = 0, poison: Optional[float] = 6.0e4,
-                device="cuda") -> Built:
+                device="cuda", flags: int = 0) -> Built:
     """Draw K/V rows and push them into a fresh cache through sparq_kv_append: one bulk call with
     per-sequence row counts, then `single_appends` one-row calls for the last rows."""
     seq = W.draw_seq_lens(w) if seq_lens is None else seq_lens.to(torch.int32)
     n_rows = int(seq.max())
     S_max = W.round_up(max(n_rows, 1), 64) if S_max is None else S_max
     K_src, V_src = W.draw_kv(w, device, n_rows=max(n_rows, 1), v_offset=v_offset, dup_rows=dup_rows)
-    cache = DecodeCache(w.B, w.H, w.H_kv, S_max, w.d_h, w.r, w.k, w.torch_dtype, device=device, poison=poison)
+    cache = DecodeCache(w.B, w.H, w.H_kv, S_max, w.d_h, w.r, w.k, w.torch_dtype, device=device, poison=poison, flags=flags)
     tail = min(single_appends, int(seq.min()))
     bulk = (seq - tail).clamp(min=0)
     if int(bulk.max()) > 0:
@@ -83,13 +83,15 @@ def check_cache_state(b: Built):
     """K, V rows and Kt columns bit-exact; v_mean within VMEAN_TOL of the fp64 mean; seq_lens."""
     c = b.cache
     Kh, Vh = host_cache_codes(b, c.S_max)
-    Kd, Vd, Ktd = W.to_codes(c.K), W.to_codes(c.V), W.to_codes(c.Kt)
+    Kd, Vd = W.to_codes(c.K), W.to_codes(c.V)
+    Ktd = None if c.Kt is None else W.to_codes(c.Kt)          # a single-copy cache has no Kt
     assert c.seq_lens.cpu().tolist() == b.seq_lens.tolist()
     for i in range(b.w.B):
         s = int(b.seq_lens[i])
         assert np.array_equal(Kd[i, :, :s], Kh[i, :, :s]), "K rows"
         assert np.array_equal(Vd[i, :, :s], Vh[i, :, :s]), "V rows"
-        assert np.array_equal(Ktd[i, :, :, :s], np.swapaxes(Kh[i, :, :s], -1, -2)), "Kt columns"
+        if Ktd is not None:
+            assert np.array_equal(Ktd[i, :, :, :s], np.swapaxes(Kh[i, :, :s], -1, -2)), "Kt columns"
     vbar = O.mean_value(Vh, b.seq_lens.numpy(), dtype=b.w.dtype_code)
     err = np.abs(c.v_mean.cpu().numpy().astype(np.float64) - vbar).max()
     assert err <= VMEAN_TOL, f"v_mean error {err}"

@@ -28,7 +28,7 @@ def say(*a):
 def run(w, *, n_q=1, q_scale=1.0, tie_channels=0, flags=0, local_window=0, **build_kw):
     say(f"[case] {w.name} B={w.B} H={w.H}/{w.H_kv} d_h={w.d_h} S={w.S} r={w.r} k={w.k} {w.dtype} "
         f"ragged={w.ragged} q_scale={q_scale} flags={flags} l={local_window} {build_kw}")
-    b = Hn.build_cache(w, **build_kw)
+    b = Hn.build_cache(w, flags=flags & B.SPARQ_FLAG_SINGLE_K, **build_kw)     # a single-copy cache gets no Kt at all
     q = W.draw_queries(w, b.K_src, b.seq_lens, n=n_q, q_scale=q_scale, tie_channels=tie_channels)
     stats = None
     for i in range(n_q):
@@ -383,3 +383,44 @@ def test_local_window_with_the_one_call_step():
     b.cache.with_params(w.r, w.k, 0, 8)
     again = b.cache.decode(q)
     assert (out.float() - again.float()).abs().max().item() <= 2e-3
+
+
+# ------------------------------------------------------------------ key cache stored once
+
+@pytest.mark.parametrize("name,kw,extra", [
+    ("1k_mha", dict(B=2, H=4, H_kv=4, d_h=128, S=3000, r=32, k=256, dtype="f16"), {}),
+    ("1k_gqa_bf16", dict(B=2, H=8, H_kv=2, d_h=128, S=2100, r=16, k=128, dtype="bf16"), {}),
+    ("1k_d64", dict(B=3, H=2, H_kv=2, d_h=64, S=777, r=8, k=64, dtype="f16"), {}),
+    ("1k_d256_long", dict(B=1, H=2, H_kv=2, d_h=256, S=20000, r=64, k=1024, dtype="bf16"), {}),
+    ("1k_window", dict(B=2, H=4, H_kv=4, d_h=128, S=1000, r=16, k=64, dtype="f16"), dict(local_window=16)),
+    ("1k_short", dict(B=4, H=2, H_kv=2, d_h=128, S=70, r=16, k=100, dtype="f16"), {}),
+])
+def test_single_copy_key_cache(name, kw, extra):
+    """SPARQ_FLAG_SINGLE_K: Section 6.1's '1 x K' variant.  The cache is built without a second key copy
+    (appends write none) and Step 1 reads the rows of K."""
+    w = W.Workload(name, seed=70, **kw)
+    seq = torch.tensor([max(1, w.S - 41 * i) for i in range(w.B)], dtype=torch.int32)
+    st = run(w, flags=B.SPARQ_FLAG_SINGLE_K, q_scale=0.02, v_offset=True, seq_lens=seq, single_appends=3, **extra)
+    assert st["exact_sets"] >= 0
+
+
+def test_single_copy_step_and_refusals():
+    w = W.Workload("1k_step", 2, 4, 2, 128, 600, 16, 48, "f16", seed=71)
+    b = Hn.build_cache(w, v_offset=True, flags=B.SPARQ_FLAG_SINGLE_K)
+    assert b.cache.Kt is None
+    kn, vn = W.draw_kv(W.scaled(w, seed=81), "cuda", n_rows=1, v_offset=True)
+    q = W.draw_queries(w, b.K_src, b.seq_lens, q_scale=0.02)[0]
+    out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q)
+    torch.cuda.synchronize()
+    assert b.cache.seq_lens.cpu().tolist() == [601, 601] and b.cache.error_flags() == 0
+    grown = Hn.Built(w, b.cache, torch.cat([b.K_src, kn], dim=2), torch.cat([b.V_src, vn], dim=2), b.seq_lens + 1, None)
+    say(Hn.compare_decode(grown, q, flags=B.SPARQ_FLAG_SINGLE_K))
+    again = b.cache.decode(q)
+    assert torch.equal(out.view(torch.int16), again.view(torch.int16))
+    # without the flag a cache that has no Kt is refused; the grouped-query rule has no single-copy kernel
+    with pytest.raises(B.SparqError) as e:
+        b.cache.with_params(w.r, w.k, 0).decode(q)
+    assert e.value.status == B.SPARQ_EINVAL
+    with pytest.raises(B.SparqError) as e:
+        b.cache.with_params(w.r, w.k, B.SPARQ_FLAG_SINGLE_K | B.SPARQ_FLAG_GQA_SHARED).decode(q)
+    assert e.value.status == B.SPARQ_EUNSUPPORTED
