@@ -1,0 +1,71 @@
+"""HIP graph capture of the decode step (GPU).  The library allocates nothing, never synchronises and
+clears its control words with a kernel, so a step can be recorded into a graph; what is recorded here is
+two consecutive steps (the ping-pong of the length / mean buffers returns to its start after two), for
+the one-launch kernel and for the multi-launch split-sequence plan.  Every replay is checked against a
+twin cache stepped eagerly, with eager work and synchronisations between the replays."""
+import pytest
+import torch
+
+import harness as Hn
+from paper_2312_04985_amd import binding as B
+from paper_2312_04985_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("graph_fused", dict(B=4, H=4, H_kv=4, d_h=128, S=1500, r=16, k=128, dtype="f16")),
+    ("graph_split", dict(B=1, H=4, H_kv=4, d_h=128, S=9000, r=32, k=256, dtype="bf16")),
+    ("graph_gqa_shared", dict(B=2, H=8, H_kv=2, d_h=128, S=1200, r=16, k=96, dtype="f16")),
+])
+def test_replayed_steps_match_eager_steps(name, kw):
+    w = W.Workload(name, seed=90, **kw)
+    flags = B.SPARQ_FLAG_GQA_SHARED if "shared" in name else 0
+    S_max = W.round_up(w.S + 16, 64)
+    g_side = Hn.build_cache(w, S_max=S_max, v_offset=True, poison=None)
+    e_side = Hn.build_cache(w, S_max=S_max, v_offset=True, poison=None)
+    for side in (g_side, e_side):
+        side.cache.with_params(w.r, w.k, flags)
+    rows_k, rows_v = W.draw_kv(W.scaled(w, seed=91), "cuda", n_rows=8, v_offset=True)
+    qs = W.draw_queries(w, g_side.K_src, g_side.seq_lens, n=8, q_scale=0.02)
+    shape3 = (w.B, w.H_kv, w.d_h)
+    k_in = [torch.empty(shape3, dtype=w.torch_dtype, device="cuda") for _ in range(2)]
+    v_in = [torch.empty(shape3, dtype=w.torch_dtype, device="cuda") for _ in range(2)]
+    q_in = [torch.empty((w.B, w.H, w.d_h), dtype=w.torch_dtype, device="cuda") for _ in range(2)]
+    out = [torch.empty((w.B, w.H, w.d_h), dtype=w.torch_dtype, device="cuda") for _ in range(2)]
+
+    def load_inputs(t):
+        for i in range(2):
+            k_in[i].copy_(rows_k[:, :, t + i]); v_in[i].copy_(rows_v[:, :, t + i]); q_in[i].copy_(qs[t + i])
+
+    # one eager pair on both sides first: it creates the second (v_mean, seq_lens) pair outside the capture
+    load_inputs(0)
+    for side in (g_side, e_side):
+        for i in range(2):
+            side.cache.step(k_in[i], v_in[i], q_in[i], out=out[i])
+    torch.cuda.synchronize()
+
+    graph = torch.cuda.CUDAGraph()
+    load_inputs(2)
+    with torch.cuda.graph(graph):
+        for i in range(2):
+            g_side.cache.step(k_in[i], v_in[i], q_in[i], out=out[i])
+    # the capture only records: bring the graph side to the state after steps 2 and 3 by replaying
+    for rep, t in enumerate((2, 4, 6)):
+        load_inputs(t)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [o.clone() for o in out]
+        want = [e_side.cache.step(k_in[i], v_in[i], q_in[i]) for i in range(2)]
+        e_side.cache.dense(q_in[0])          # eager work of the program between replays
+        torch.cuda.synchronize()
+        for i in range(2):
+            assert torch.equal(got[i].view(torch.int16), want[i].view(torch.int16)), (name, rep, i)
+        assert torch.equal(g_side.cache.seq_lens, e_side.cache.seq_lens)
+        assert torch.equal(g_side.cache.v_mean, e_side.cache.v_mean)
+    assert g_side.cache.error_flags() == 0 and e_side.cache.error_flags() == 0
+    n = w.S + 8
+    assert g_side.cache.seq_lens.cpu().tolist() == [n] * w.B
+    assert torch.equal(g_side.cache.K[:, :, :n], e_side.cache.K[:, :, :n])
+    assert torch.equal(g_side.cache.Kt[:, :, :, :n], e_side.cache.Kt[:, :, :, :n])
+    assert torch.equal(g_side.cache.V[:, :, :n], e_side.cache.V[:, :, :n])
