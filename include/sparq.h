@@ -22,6 +22,11 @@
  *   seq_lens [B]                   int32, S_b
  * S_max must be a multiple of 64 and every pointer 16-byte aligned.  d_h is 64, 128 or
  * 256.  Rows at positions >= S_b are never read.
+ * Kt is maintained by this library only, and 8 positions at a time: its columns below
+ * 8 * floor(S_b / 8) equal K transposed; the up to 7 newest keys reach it when the eighth
+ * arrives (one aligned 16-byte store per channel row instead of eight scattered 2-byte
+ * stores) and until then Step 1 takes them from the rows of K.  Columns from
+ * 8 * floor(S_b / 8) on are unspecified.
  */
 #ifndef SPARQ_H
 #define SPARQ_H
@@ -111,8 +116,8 @@ int sparq_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stre
  *   n_new          rows per sequence in k_new / v_new (>= 1)
  *   n_new_per_seq  device [B] or NULL: sequence b appends only its first
  *                  n_new_per_seq[b] rows (0..n_new); NULL appends n_new everywhere
- * For sequence b with n rows: rows land at positions S_b..S_b+n-1 of K and V and in the
- * matching columns of Kt, v_mean becomes the mean of the S_b+n value rows, seq_lens[b]
+ * For sequence b with n rows: rows land at positions S_b..S_b+n-1 of K and V, Kt is brought
+ * up to date to column 8 * floor((S_b+n) / 8) at least, v_mean becomes the mean of the S_b+n value rows, seq_lens[b]
  * += n.  If S_b + n > S_max the sequence is left untouched and SPARQ_ERR_APPEND_FULL is
  * raised in the error word.  The only call that mutates the cache.
  */
@@ -149,7 +154,8 @@ int sparq_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
  * over the cache including the new token), except that the small state is not updated in place:
  * the new lengths and means are written to seq_lens_next [B] and v_mean_next [B, H_kv, d_h]
  * (device, must not alias cache->seq_lens / cache->v_mean, which are only read) and the caller
- * swaps the two pairs of buffers between steps.  K, V and Kt receive row S_b in place.  The new
+ * swaps the two pairs of buffers between steps.  K and V receive row S_b in place, Kt as in
+ * sparq_kv_append.  The new
  * row is taken from k_new / v_new [B, H_kv, d_h] by every head, so no head depends on another
  * one's write.  A sequence with S_b = S_max is decoded without the new row, keeps its length
  * and mean, and raises SPARQ_ERR_APPEND_FULL.  Other arguments as for sparq_decode.

@@ -195,6 +195,52 @@ __device__ __forceinline__ void stream_channel_rows(const char* Kt_head, size_t 
 }
 
 // ------------------------------------------------------------------------------------------------
+// The newest S mod 8 keys of a sequence.  The S-contiguous copy Kt is brought up to date 8 positions at
+// a time (one aligned 16-byte store per channel row every 8th append, instead of a 2-byte store per
+// channel on every append: those cost a 32-byte memory transaction each).  Positions 8 floor(S/8) .. S-1
+// therefore are not in Kt yet; there are at most 7 of them and their approximate logit numerators come
+// from the rows of K: wave w takes position 8 floor(S/8) + w, lane l the channels l, l + 64, ... of the
+// padded list.  The loads are issued before Step 1b streams Kt and used after it.
+struct TailRow {
+  uint16_t raw[4];   // up to 256 list entries over 64 lanes
+};
+
+__device__ __forceinline__ TailRow tail_row_issue(const uint16_t* krow, const int* chan, int r8, int lane) {
+  TailRow t;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int jj = lane + i * kWave;
+    t.raw[i] = jj < r8 ? krow[chan[jj]] : (uint16_t)0;
+  }
+  return t;
+}
+
+template <class T>
+__device__ __forceinline__ float tail_row_dot(const TailRow& t, const float* qs, int r8, int lane) {
+  float part = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int jj = lane + i * kWave;
+    if (jj < r8) part = fmaf(T::widen(t.raw[i]), qs[jj], part);
+  }
+  return wave_sum(part);
+}
+
+// Columns S-8 .. S-1 of Kt for channel j of one KV head, S a multiple of 8: rows S-8 .. S-2 of K (cached
+// by earlier calls) and `newest`, the code of the row being appended.  One 16-byte store.
+__device__ __forceinline__ void flush_key_columns(uint16_t* Kt_head, const uint16_t* K_head, int S_max, int d_h,
+                                                  int S, int j, uint16_t newest) {
+  uint32_t w[4];
+#pragma unroll
+  for (int e = 0; e < 8; e += 2) {
+    const uint32_t lo = K_head[(size_t)(S - 8 + e) * d_h + j];
+    const uint32_t hi = e + 1 < 7 ? K_head[(size_t)(S - 8 + e + 1) * d_h + j] : (uint32_t)newest;
+    w[e >> 1] = lo | (hi << 16);
+  }
+  *reinterpret_cast<uint4*>(Kt_head + (size_t)j * S_max + (S - 8)) = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// ------------------------------------------------------------------------------------------------
 // Step 2a: the kq positions with the largest keys (ties to the lower position)
 
 struct SelectLds {

@@ -1,7 +1,6 @@
 // Cache maintenance: append key/value rows, keep the S-contiguous key copy and the running
 // mean value vector in step (Section 3 "Mean value reallocation"; Appendix F "Storing K twice").
-#include "common.h"
-#include "params.h"
+#include "decode_stages.h"
 
 namespace sparq {
 
@@ -42,12 +41,15 @@ __global__ __launch_bounds__(512) void append_one_row(const AppendArgs a) {
     *reinterpret_cast<uint4*>(Krow) = kc;
     *reinterpret_cast<uint4*>(Vrow) = vc;
     // the same 8 key elements go down column S of the S-contiguous copy (2-byte stores)
-    if (a.Kt) {   // null: the cache keeps K once
-      uint16_t* Ktcol = reinterpret_cast<uint16_t*>(a.Kt) + (head * a.d_h + j0) * a.S_max + S;
+    // the S-contiguous copy advances 8 positions at a time: when this row completes a group of 8, the
+    // thread writes columns S-7 .. S of its 8 channels (rows S-7 .. S-1 come back from K)
+    if (a.Kt && ((S + 1) & 7) == 0) {   // null: the cache keeps K once
       const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w};
 #pragma unroll
       for (int e = 0; e < 8; ++e)
-        Ktcol[(size_t)e * a.S_max] = (uint16_t)((e & 1) ? (kw[e >> 1] >> 16) : (kw[e >> 1] & 0xffffu));
+        flush_key_columns(reinterpret_cast<uint16_t*>(a.Kt) + head * a.d_h * (size_t)a.S_max,
+                          reinterpret_cast<const uint16_t*>(a.K) + head * a.S_max * (size_t)a.d_h, a.S_max, a.d_h, S + 1,
+                          j0 + e, (uint16_t)((e & 1) ? (kw[e >> 1] >> 16) : (kw[e >> 1] & 0xffffu)));
     }
     // running mean: v_mean += (v - v_mean) / (S + 1)
     const float* vm = a.v_mean + head * a.d_h + j0;
@@ -114,6 +116,16 @@ __global__ __launch_bounds__(BT) void append_rows(const AppendArgs a) {
       for (int j = wave; j < DH; j += BT / 64)
         if (lane < rows) Ktdst[(size_t)j * a.S_max + n0 + lane] = tile[lane * LD + j];
     __syncthreads();
+  }
+  // the up to 7 rows that were cached before this call and not yet in the S-contiguous copy
+  if (a.Kt) {
+    const int S_fl = S & ~7;
+    const uint16_t* Khead = reinterpret_cast<const uint16_t*>(a.K) + head * a.S_max * (size_t)DH;
+    uint16_t* Kthead = reinterpret_cast<uint16_t*>(a.Kt) + head * DH * (size_t)a.S_max;
+    for (int i = tid; i < (S - S_fl) * DH; i += BT) {
+      const int e = i / DH, j = i - e * DH;
+      Kthead[(size_t)j * a.S_max + S_fl + e] = Khead[(size_t)(S_fl + e) * DH + j];
+    }
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) colsum[prow][sub * 8 + e] = sum[e];

@@ -119,36 +119,45 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   const float tau = apply_tau_mode(select_channels<T, DH>(L.qry, qcode, a.r, tid, lane, wave), a.flags, DH, a.r);
   const Window win = make_window(a.local_window, S, kq);
   if (a.chan_out && tid < a.r) a.chan_out[(size_t)u * a.r + tid] = L.qry.chan[tid];
-  float dot_new = 0.0f;   // approximate logit numerator of the appended row (every wave computes it)
-  if (APPEND && appended) {
-    float part_new = 0.0f;
-    for (int jj = lane; jj < ((a.r + 7) & ~7); jj += kWave)
-      part_new = fmaf(T::widen(L.knew[L.qry.chan[jj]]), L.qry.qs[jj], part_new);
-    dot_new = wave_sum(part_new);
+  // the newest S mod 8 positions are not in Kt: wave w gets position S_fl + w from its K row (from the
+  // inputs if it is the row being appended); loads issued here, used after stage 1
+  // (in the one-launch step Kt is up to date for the length before this call: the group of 8 that the new
+  // row may complete is written at the end of this launch, so up to 8 positions come from rows)
+  const int S_fl = ((APPEND && appended) ? S - 1 : S) & ~7, n_tail = S - S_fl, r8 = (a.r + 7) & ~7;
+  const uint16_t* K_rows = reinterpret_cast<const uint16_t*>(a.K) + kv_head * a.S_max * (size_t)DH;
+  TailRow tail;
+  const bool tail_is_new = APPEND && appended && wave == n_tail - 1;
+  if (wave < n_tail) {
+    if (tail_is_new) tail = tail_row_issue(L.knew, L.qry.chan, r8, lane);
+    else tail = tail_row_issue(K_rows + (size_t)(S_fl + wave) * DH, L.qry.chan, r8, lane);
   }
 
   // ---------------- stage 1 ----------------
   const size_t row_bytes = (size_t)a.S_max * 2;
   const char* Kt_head = reinterpret_cast<const char*>(a.Kt) + kv_head * DH * row_bytes;
   float tmax = -INFINITY;
-  stream_channel_rows<T>(Kt_head, row_bytes, L.qry.chan, L.qry.qs, a.r, 0, (S + 7) >> 3, tid,
+  stream_channel_rows<T>(Kt_head, row_bytes, L.qry.chan, L.qry.qs, a.r, 0, S_fl >> 3, tid,
                          [&](int c, const float (&acc)[8]) {
     uint32_t kx[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      if (c * 8 + e < S) {
-        const float val = (APPEND && appended && c * 8 + e == S - 1) ? dot_new : acc[e];
-        tmax = fmaxf(tmax, val);
-        kx[e] = float_to_key(val);
-        if (c * 8 + e < win.S_old) atomicAdd(&L.sel.hist[hist_slot(kx[e] >> 21)], 1u);
-      } else {
-        kx[e] = 0u;
-      }
+      tmax = fmaxf(tmax, acc[e]);
+      kx[e] = float_to_key(acc[e]);
+      if (c * 8 + e < win.S_old) atomicAdd(&L.sel.hist[hist_slot(kx[e] >> 21)], 1u);
     }
     uint4* dst = reinterpret_cast<uint4*>(L.keys + c * 8);
     dst[0] = make_uint4(kx[0], kx[1], kx[2], kx[3]);
     dst[1] = make_uint4(kx[4], kx[5], kx[6], kx[7]);
   });
+  if (wave < n_tail) {
+    const float dot = tail_row_dot<T>(tail, L.qry.qs, r8, lane);
+    tmax = fmaxf(tmax, dot);
+    if (lane == 0) {
+      const uint32_t key = float_to_key(dot);
+      L.keys[S_fl + wave] = key;
+      if (S_fl + wave < win.S_old) atomicAdd(&L.sel.hist[hist_slot(key >> 21)], 1u);
+    }
+  }
   tmax = wave_max(tmax);
   if (lane == 0) L.sel.red[wave] = tmax;
   __syncthreads();
@@ -208,7 +217,9 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
       reinterpret_cast<uint4*>(Krow)[tid] = reinterpret_cast<const uint4*>(L.knew)[tid];
       reinterpret_cast<uint4*>(Vrow)[tid] = reinterpret_cast<const uint4*>(L.vnew)[tid];
     }
-    if (tid < DH) reinterpret_cast<uint16_t*>(a.Kt)[(kv_head * DH + tid) * a.S_max + (S - 1)] = L.knew[tid];
+    // the S-contiguous copy advances 8 positions at a time
+    if ((S & 7) == 0 && tid < DH)
+      flush_key_columns(reinterpret_cast<uint16_t*>(a.Kt) + kv_head * DH * (size_t)a.S_max, K_rows, a.S_max, DH, S, tid, L.knew[tid]);
   }
 }
 

@@ -234,7 +234,17 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
   // ---------------- pass A: per-head max and sum-exp of the approximate logits ----------------
   const size_t row_bytes = (size_t)a.S_max * 2;
   const char* Kt_head = reinterpret_cast<const char*>(a.Kt) + kv_head * DH * row_bytes;
-  const int n_chunks = (S + 7) >> 3;
+  const int n_chunks = S >> 3;   // whole chunks; the newest S mod 8 positions are not in Kt yet
+  const int S_fl = S & ~7, n_tail = S - S_fl, r8 = (a.r + 7) & ~7;
+  float tdot[G];          // wave w: the logit numerators of position S_fl + w for the G heads, from its K row
+#pragma unroll
+  for (int h = 0; h < G; ++h) tdot[h] = 0.0f;
+  if (wave < n_tail) {
+    const TailRow tail = tail_row_issue(reinterpret_cast<const uint16_t*>(a.K) + (kv_head * a.S_max + S_fl + wave) * (size_t)DH,
+                                        L.chan, r8, lane);
+#pragma unroll
+    for (int h = 0; h < G; ++h) tdot[h] = tail_row_dot<T>(tail, L.qs + h * DH, r8, lane);
+  }
   float mt[G], zt[G];   // running max of the logit numerator, sum of exp2((d - max) * esc)
 #pragma unroll
   for (int h = 0; h < G; ++h) { mt[h] = -INFINITY; zt[h] = 0.0f; }
@@ -252,6 +262,14 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
       }
     }
   });
+  if (wave < n_tail && lane == 0) {
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      const float v = tdot[h];
+      if (v > mt[h]) { zt[h] = zt[h] * exp2f((mt[h] - v) * esc[h]) + 1.0f; mt[h] = v; }
+      else zt[h] += exp2f((v - mt[h]) * esc[h]);
+    }
+  }
   float mh[G], inv_z[G];
 #pragma unroll
   for (int h = 0; h < G; ++h) {
@@ -300,6 +318,14 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
     dst[0] = make_uint4(kx[0], kx[1], kx[2], kx[3]);
     dst[1] = make_uint4(kx[4], kx[5], kx[6], kx[7]);
   });
+  if (wave < n_tail && lane == 0) {
+    float score = 0.0f;
+#pragma unroll
+    for (int h = 0; h < G; ++h) score += exp2f((tdot[h] - mh[h]) * esc[h]) * inv_z[h];
+    const uint32_t key = float_to_key(score);
+    L.keys[S_fl + wave] = key;
+    if (S_fl + wave < win.S_old) atomicAdd(&L.sel.hist[hist_slot(key >> 21)], 1u);
+  }
   __syncthreads();
 
   // ---------------- stage 2: the kq positions of largest group score ----------------

@@ -66,8 +66,14 @@ __global__ __launch_bounds__(NT, 4) void split_scores(const SplitArgs a) {
     if (tid == 0) a.tau_ws[u] = tau;
   }
 
-  // this workgroup's slice of the 8-position chunks
-  const int n_chunks = (S + 7) >> 3;
+  // the newest S mod 8 positions are not in Kt: the last slice takes them from the rows of K
+  const int S_fl = S & ~7, n_tail = s == a.n_split - 1 ? S - S_fl : 0, r8 = (d.r + 7) & ~7;
+  TailRow tail;
+  if (wave < n_tail)
+    tail = tail_row_issue(reinterpret_cast<const uint16_t*>(d.K) + (kv_head * d.S_max + S_fl + wave) * (size_t)DH, chan, r8, lane);
+
+  // this workgroup's slice of the whole 8-position chunks
+  const int n_chunks = S >> 3;
   const int per = (n_chunks + a.n_split - 1) / a.n_split;
   const int c0 = s * per < n_chunks ? s * per : n_chunks;
   const int c1 = c0 + per < n_chunks ? c0 + per : n_chunks;
@@ -79,17 +85,18 @@ __global__ __launch_bounds__(NT, 4) void split_scores(const SplitArgs a) {
     uint32_t kx[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      if (c * 8 + e < S) {
-        tmax = fmaxf(tmax, acc[e]);
-        kx[e] = float_to_key(acc[e]);
-      } else {
-        kx[e] = 0u;
-      }
+      tmax = fmaxf(tmax, acc[e]);
+      kx[e] = float_to_key(acc[e]);
     }
     uint4* dst = reinterpret_cast<uint4*>(keys + c * 8);
     dst[0] = make_uint4(kx[0], kx[1], kx[2], kx[3]);
     dst[1] = make_uint4(kx[4], kx[5], kx[6], kx[7]);
   });
+  if (wave < n_tail) {
+    const float dot = tail_row_dot<T>(tail, qs, r8, lane);
+    tmax = fmaxf(tmax, dot);
+    if (lane == 0) keys[S_fl + wave] = float_to_key(dot);
+  }
   tmax = wave_max(tmax);
   if (lane == 0) red[wave] = tmax;
   __syncthreads();

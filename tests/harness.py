@@ -80,7 +80,9 @@ def host_cache_codes(b: Built, S_max: int):
 
 
 def check_cache_state(b: Built):
-    """K, V rows and Kt columns bit-exact; v_mean within VMEAN_TOL of the fp64 mean; seq_lens."""
+    """K, V rows and Kt columns bit-exact; v_mean within VMEAN_TOL of the fp64 mean; seq_lens.
+    The library brings Kt up to date 8 positions at a time: its columns below 8 * floor(S_b / 8) must be
+    the transpose of K, the up to 7 newest ones are not looked at (the decode reads those keys from K)."""
     c = b.cache
     Kh, Vh = host_cache_codes(b, c.S_max)
     Kd, Vd = W.to_codes(c.K), W.to_codes(c.V)
@@ -91,7 +93,7 @@ def check_cache_state(b: Built):
         assert np.array_equal(Kd[i, :, :s], Kh[i, :, :s]), "K rows"
         assert np.array_equal(Vd[i, :, :s], Vh[i, :, :s]), "V rows"
         if Ktd is not None:
-            assert np.array_equal(Ktd[i, :, :, :s], np.swapaxes(Kh[i, :, :s], -1, -2)), "Kt columns"
+            assert np.array_equal(Ktd[i, :, :, :s & ~7], np.swapaxes(Kh[i, :, :s & ~7], -1, -2)), "Kt columns"
     vbar = O.mean_value(Vh, b.seq_lens.numpy(), dtype=b.w.dtype_code)
     err = np.abs(c.v_mean.cpu().numpy().astype(np.float64) - vbar).max()
     assert err <= VMEAN_TOL, f"v_mean error {err}"
@@ -281,7 +283,7 @@ def compare_sampled(b: Built, q: torch.Tensor, *, n_units: int = 48, flags: int 
         # cache state of this head: both key layouts bit-exact
         assert np.array_equal(W.to_codes(c.K[bi, hk, :s]), Kh[i, 0, :s]), "K rows"
         assert np.array_equal(W.to_codes(c.V[bi, hk, :s]), Vh[i, 0, :s]), "V rows"
-        assert np.array_equal(W.to_codes(c.Kt[bi, hk, :, :s]), Kh[i, 0, :s].T), "Kt columns"
+        assert np.array_equal(W.to_codes(c.Kt[bi, hk, :, :s & ~7]), Kh[i, 0, :s & ~7].T), "Kt columns (up to date 8 at a time)"
         g_out[i] = sub(out.float(), bi, hk); g_alpha[i] = sub(alpha, bi, hk)
         g_idx[i] = sub(idx, bi, hk); g_chan[i] = sub(chan, bi, hk)
         if with_dense:

@@ -166,12 +166,19 @@ def test_append_to_a_full_sequence_raises_the_flag_and_leaves_it_untouched():
     assert b.cache.seq_lens.cpu().tolist() == [64, 41]
     for t0, t1 in zip(before, (b.cache.K, b.cache.Kt, b.cache.V, b.cache.v_mean)):
         assert torch.equal(t0[0], t1[0])
-    assert torch.equal(b.cache.K[1, :, 40], extra_k[1, :, 0]) and torch.equal(b.cache.Kt[1, :, :, 40], extra_k[1, :, 0])
+    assert torch.equal(b.cache.K[1, :, 40], extra_k[1, :, 0])
+    # the S-contiguous copy catches up when the 8th row of a group arrives (position 47)
+    for i in range(7):
+        assert not torch.equal(b.cache.Kt[1, :, :, 40:48], b.cache.K[1, :, 40:48].transpose(-1, -2))
+        b.cache.append(extra_k[:, :, 0].contiguous() * (i + 2), extra_v[:, :, 0].contiguous())
+    torch.cuda.synchronize()
+    assert b.cache.seq_lens.cpu().tolist() == [64, 48]
+    assert torch.equal(b.cache.Kt[1, :, :, :48], b.cache.K[1, :, :48].transpose(-1, -2))
     # bulk append past the end behaves the same
     many_k, many_v = W.draw_kv(W.scaled(w, seed=98), "cuda", n_rows=30)
     b.cache.append(many_k, many_v)
     torch.cuda.synchronize()
-    assert b.cache.error_flags() == B.SPARQ_ERR_APPEND_FULL and b.cache.seq_lens.cpu().tolist() == [64, 41]
+    assert b.cache.error_flags() == B.SPARQ_ERR_APPEND_FULL and b.cache.seq_lens.cpu().tolist() == [64, 48]
 
 
 def test_long_running_mean_drift():
@@ -314,7 +321,11 @@ def test_decode_step_on_a_full_sequence():
     assert b.cache.error_flags() == B.SPARQ_ERR_APPEND_FULL
     assert b.cache.seq_lens.cpu().tolist() == [64, 31]
     assert torch.equal(out[0].view(torch.int16), ref[0].view(torch.int16)) and torch.equal(b.cache.v_mean[0], vm0[0])
-    assert torch.equal(b.cache.K[1, :, 30], kn[1, :, 0]) and torch.equal(b.cache.Kt[1, :, :, 30], kn[1, :, 0])
+    assert torch.equal(b.cache.K[1, :, 30], kn[1, :, 0])
+    out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q)      # row 31 completes a group of 8
+    torch.cuda.synchronize()
+    assert b.cache.seq_lens.cpu().tolist() == [64, 32]
+    assert torch.equal(b.cache.Kt[1, :, :, :32], b.cache.K[1, :, :32].transpose(-1, -2))
 
 
 # ------------------------------------------------------------------ split-sequence plan (few heads, long cache)
