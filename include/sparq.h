@@ -136,7 +136,8 @@ int sparq_kv_append(const sparq_shape* shape, const sparq_cache* cache, const vo
  *   Step 3  alpha = sum_{i in i2} s_hat_i;  y = alpha y3 + (1 - alpha) v_mean
  * Arithmetic is fp32 on the 16-bit inputs; `out` is rounded to nearest-even.
  *   q          device [B, H, d_h]
- *   k_per_seq  device [B] or NULL; k_per_seq[b] replaces shape.k for sequence b
+ *   k_per_seq  device [B] or NULL; k_per_seq[b] in 1..shape.k replaces shape.k for sequence b
+ *              (shape.k is the maximum that buffers are sized for: values outside are clamped)
  *   out        device [B, H, d_h], cache dtype
  *   alpha_out  device [B, H] fp32 or NULL
  *   idx_out    device [B, H, idx_stride] int32 or NULL: i2 ascending, padded with -1

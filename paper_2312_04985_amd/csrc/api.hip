@@ -67,7 +67,7 @@ bool split_plan(const sparq_shape* s, int* n_split) {
 }
 
 // workspace: [0, kControlBytes) control block (error word, arrival counters), then either the
-// dense_decode partials or the arrays of the split-sequence plan (they are never live together)
+// dense_decode partials or the arrays of the split-sequence / long-sequence plan (never live together)
 struct SplitLayout { size_t tmax, tau, alpha, keys, list, part, end; };
 
 SplitLayout split_layout(const sparq_shape* s, int n_split) {
@@ -84,29 +84,14 @@ SplitLayout split_layout(const sparq_shape* s, int n_split) {
   return l;
 }
 
-size_t workspace_need(const sparq_shape* s) {
-  int n_split, rows;
-  dense_plan(s, &n_split, &rows);
-  size_t need = (size_t)kControlBytes + (size_t)s->B * s->H * n_split * (s->d_h + 2) * sizeof(float);
-  int ns;
-  if (split_plan(s, &ns)) {
-    const size_t e = split_layout(s, ns).end;
-    if (e > need) need = e;
-  }
-  return need;
-}
-
-int check_workspace(const sparq_shape* s, const void* ws, size_t bytes) {
-  if (!ws || !aligned16(ws) || bytes < workspace_need(s)) return SPARQ_EWORKSPACE;
-  return SPARQ_OK;
-}
-
+// LDS a workgroup may use: the device's, or gfx950's 160 KiB where no device can be asked (sizing
+// queries on a machine without a GPU)
 int max_lds_bytes() {
   static int cached = -1;   // same for every device of one machine; benign race
   if (cached < 0) {
     int dev = 0, v = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
-    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 160 * 1024;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return 160 * 1024;
     cached = v;
   }
   return cached;
@@ -120,12 +105,94 @@ bool wants_shared(const sparq_shape* shape) {
 
 bool single_k(const sparq_shape* shape) { return (shape->flags & SPARQ_FLAG_SINGLE_K) != 0; }
 
+// Which kernels serve a shape.  Every plan keeps one 4-byte key per position (or per candidate) of its
+// unit of work in LDS; that decides what fits.
+enum Plan { kPlanNone, kPlanFused, kPlanSplit, kPlanLong, kPlanShared, kPlanSingleK };
+struct PlanInfo { Plan plan; int n_split, n_span, span_len, cand_cap; };
+
+// The two-level plan: spans of `span` positions select their own top-k, one workgroup per unit merges at
+// most n_span * min(k, span) candidates.  It serves what no single workgroup can hold (S_max beyond the
+// LDS), and batches with few units and long caches when a span is longer than k, i.e. when the merge sees
+// fewer keys than a select over the whole sequence would (measured against the split-sequence plan:
+// 58 vs 62 us at B = 1, 32 heads, S = 32768, k = 2048; 50 vs 63 us at k = 512; 39 vs 43 us at S = 16384).
+bool two_level_plan(const sparq_shape* s, int span, size_t lds_max, PlanInfo* p) {
+  const int64_t n_span = ((int64_t)s->S_max + span - 1) / span;
+  if (n_span > kMaxSpans) return false;
+  const int cap = s->k < span ? s->k : span;
+  if (long_scores_lds_bytes(span, s->d_h) > lds_max || long_merge_lds_bytes((int)n_span, cap) > lds_max) return false;
+  const int64_t units = (int64_t)s->B * s->H;
+  int64_t n = 512 / units;                      // gather workgroups per unit: fill the chip, >= 64 rows each
+  if (n > kMaxSplit) n = kMaxSplit;
+  if (n > s->k / 64) n = s->k / 64;
+  if (n < 1) n = 1;
+  p->n_span = (int)n_span; p->span_len = span; p->cand_cap = cap; p->n_split = (int)n;
+  return true;
+}
+
+PlanInfo choose_plan(const sparq_shape* s) {
+  PlanInfo p{kPlanNone, 0, 0, 0, 0};
+  const size_t lds_max = (size_t)max_lds_bytes();
+  if (single_k(s)) {
+    const size_t need = wants_shared(s) ? 0 : decode_single_k_lds_bytes(s->S_max, s->d_h);
+    if (need != 0 && need <= lds_max) p.plan = kPlanSingleK;
+    return p;
+  }
+  if (wants_shared(s)) {
+    const size_t need = decode_shared_lds_bytes(s->S_max, s->d_h, s->H / s->H_kv);
+    if (need != 0 && need <= lds_max) p.plan = kPlanShared;
+    return p;
+  }
+  if ((int64_t)s->B * s->H <= kSplitMaxUnits && s->S_max >= 16384) {
+    const int span = s->S_max >= 32768 ? kLongSpan : kLongSpan / 2;
+    if (s->k < span && two_level_plan(s, span, lds_max, &p)) { p.plan = kPlanLong; return p; }
+  }
+  if (split_plan(s, &p.n_split) && split_select_lds_bytes(s->S_max) <= lds_max) { p.plan = kPlanSplit; return p; }
+  if (decode_lds_bytes(s->S_max, s->d_h) <= lds_max) { p.plan = kPlanFused; return p; }
+  if (two_level_plan(s, kLongSpan, lds_max, &p)) p.plan = kPlanLong;
+  return p;
+}
+
+struct LongLayout { size_t tmax, zsum, cnt, tau, alpha, ckey, cpos, list, part, end; };
+
+LongLayout long_layout(const sparq_shape* s, const PlanInfo& p) {
+  const size_t units = (size_t)s->B * s->H;
+  LongLayout l;
+  size_t off = kControlBytes;
+  l.tmax = off; off = align256(off + units * p.n_span * sizeof(float));
+  l.zsum = off; off = align256(off + units * p.n_span * sizeof(float));
+  l.cnt = off; off = align256(off + units * p.n_span * sizeof(int32_t));
+  l.tau = off; off = align256(off + units * sizeof(float));
+  l.alpha = off; off = align256(off + units * sizeof(float));
+  l.ckey = off; off = align256(off + units * p.n_span * p.cand_cap * sizeof(uint32_t));
+  l.cpos = off; off = align256(off + units * p.n_span * p.cand_cap * sizeof(int32_t));
+  l.list = off; off = align256(off + units * s->S_max * sizeof(int32_t));
+  l.part = off; off = align256(off + units * p.n_split * (s->d_h + 2) * sizeof(float));
+  l.end = off;
+  return l;
+}
+
+size_t workspace_need(const sparq_shape* s) {
+  int n_split, rows;
+  dense_plan(s, &n_split, &rows);
+  size_t need = (size_t)kControlBytes + (size_t)s->B * s->H * n_split * (s->d_h + 2) * sizeof(float);
+  const PlanInfo p = choose_plan(s);
+  size_t e = 0;
+  if (p.plan == kPlanSplit) e = split_layout(s, p.n_split).end;
+  if (p.plan == kPlanLong) e = long_layout(s, p).end;
+  return e > need ? e : need;
+}
+
+int check_workspace(const sparq_shape* s, const void* ws, size_t bytes) {
+  if (!ws || !aligned16(ws) || bytes < workspace_need(s)) return SPARQ_EWORKSPACE;
+  return SPARQ_OK;
+}
+
 // enqueue one decode over `a` with the plan the shape calls for
 hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* workspace, hipStream_t s) {
-  int n_split = 0;
-  const bool shared = wants_shared(shape), one_k = single_k(shape);
-  const bool split = !shared && !one_k && split_plan(shape, &n_split);
-  if (!shared && !split && !one_k) return launch_decode(a, shape->dtype, s);
+  const PlanInfo p = choose_plan(shape);
+  if (p.plan == kPlanNone) return hipErrorInvalidValue;
+  if (p.plan == kPlanFused) return launch_decode(a, shape->dtype, s);
+  const bool one_k = p.plan == kPlanSingleK;
   DecodeArgs d = a;
   if (a.k_new) {
     // only the one-workgroup-per-head kernel has the append built in: append into the *_next state
@@ -141,12 +208,28 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
     d.k_new = nullptr; d.v_new = nullptr; d.v_mean_next = nullptr; d.seq_lens_next = nullptr;
   }
   if (one_k) return launch_decode_single_k(d, shape->dtype, s);
-  if (shared) return launch_decode_shared(d, shape->dtype, s);
-  const SplitLayout l = split_layout(shape, n_split);
+  if (p.plan == kPlanShared) return launch_decode_shared(d, shape->dtype, s);
   char* w = static_cast<char*>(workspace);
+  if (p.plan == kPlanLong) {
+    const LongLayout l = long_layout(shape, p);
+    LongArgs la;
+    la.d = d;
+    la.n_span = p.n_span; la.span_len = p.span_len; la.cand_cap = p.cand_cap; la.n_split = p.n_split;
+    la.tmax_ws = reinterpret_cast<float*>(w + l.tmax);
+    la.zsum_ws = reinterpret_cast<float*>(w + l.zsum);
+    la.cnt_ws = reinterpret_cast<int32_t*>(w + l.cnt);
+    la.tau_ws = reinterpret_cast<float*>(w + l.tau);
+    la.alpha_ws = reinterpret_cast<float*>(w + l.alpha);
+    la.cand_key_ws = reinterpret_cast<uint32_t*>(w + l.ckey);
+    la.cand_pos_ws = reinterpret_cast<int32_t*>(w + l.cpos);
+    la.list_ws = reinterpret_cast<int32_t*>(w + l.list);
+    la.part_ws = reinterpret_cast<float*>(w + l.part);
+    return launch_decode_long(la, shape->dtype, s);
+  }
+  const SplitLayout l = split_layout(shape, p.n_split);
   SplitArgs sa;
   sa.d = d;
-  sa.n_split = n_split;
+  sa.n_split = p.n_split;
   sa.tmax_ws = reinterpret_cast<float*>(w + l.tmax);
   sa.tau_ws = reinterpret_cast<float*>(w + l.tau);
   sa.alpha_ws = reinterpret_cast<float*>(w + l.alpha);
@@ -156,22 +239,7 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
   return launch_decode_split(sa, shape->dtype, s);
 }
 
-// every decode kernel keeps one 4-byte key per cached position in LDS
-bool decode_supported(const sparq_shape* shape) {
-  int n_split;
-  const size_t lds_max = (size_t)max_lds_bytes();
-  if (single_k(shape)) {
-    if (wants_shared(shape)) return false;
-    const size_t need = decode_single_k_lds_bytes(shape->S_max, shape->d_h);
-    return need != 0 && need <= lds_max;
-  }
-  if (wants_shared(shape)) {
-    const size_t need = decode_shared_lds_bytes(shape->S_max, shape->d_h, shape->H / shape->H_kv);
-    return need != 0 && need <= lds_max;
-  }
-  if (split_plan(shape, &n_split)) return split_select_lds_bytes(shape->S_max) <= lds_max;
-  return decode_lds_bytes(shape->S_max, shape->d_h) <= lds_max;
-}
+bool decode_supported(const sparq_shape* shape) { return choose_plan(shape).plan != kPlanNone; }
 
 }  // namespace
 

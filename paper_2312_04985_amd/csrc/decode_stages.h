@@ -316,12 +316,15 @@ __device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wsum, 
 // Ends with a barrier that also publishes the list.  esc = log2(e) / tau.  With WITH_ALPHA = false only
 // the list is produced (the grouped-query kernel gets alpha per query head elsewhere) and 0 is returned.
 // Positions >= forced_from (the local window) are taken whatever their keys; the predicate applies to
-// the positions before them.
+// the positions before them.  Optional: key_out[n] receives the key of the n-th selected entry, the
+// entries written to list / idx_out are offset by pos_base, sums_out[0..1] receive the denominator and the
+// numerator of alpha.
 template <bool WITH_ALPHA = true>
 __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t* list, int S, int forced_from,
                                                   uint32_t pmask, uint32_t pval, int need, float dmax, float esc,
                                                   int32_t* idx_out, int idx_stride, const SelectLds& sl, int tid,
-                                                  int lane, int wave) {
+                                                  int lane, int wave, uint32_t* key_out = nullptr, int pos_base = 0,
+                                                  float* sums_out = nullptr) {
   const int n_chunks = (S + 7) >> 3;
   float zsum = 0.0f, asum = 0.0f;
   uint32_t run_gt = 0, run_eq = 0;
@@ -363,8 +366,9 @@ __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t
         if ((eq_bits >> e) & 1u) { take = eq_before < (uint32_t)need; ++eq_before; }
         if (take) {
           asum += w;
-          list[o] = (uint32_t)(c * 8 + e);
-          if (idx_out && (int)o < idx_stride) idx_out[o] = c * 8 + e;
+          list[o] = (uint32_t)(pos_base + c * 8 + e);
+          if (key_out) key_out[o] = kx[e];
+          if (idx_out && (int)o < idx_stride) idx_out[o] = pos_base + c * 8 + e;
           ++o;
         }
       }
@@ -382,6 +386,7 @@ __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t
   float zt = 0.0f, at = 0.0f;
 #pragma unroll
   for (int w = 0; w < NW; ++w) { zt += sl.red[w]; at += sl.red[NW + w]; }
+  if (sums_out) { sums_out[0] = zt; sums_out[1] = at; }
   return at / zt;
 }
 

@@ -41,6 +41,27 @@ struct DenseArgs {
 };
 
 // split-sequence plan (few heads, long sequences): workspace arrays and the split count
+// two-level plan: spans of span_len positions (a multiple of 64, at most kLongSpan), at most kMaxSpans per sequence
+constexpr int kLongSpan = 8192;
+constexpr int kMaxSpans = 64;
+
+struct LongArgs {
+  DecodeArgs d;
+  int32_t n_span;          // workgroups per (sequence, head) in the scoring launch
+  int32_t span_len;        // positions per span
+  int32_t cand_cap;        // candidates one span may hand on = min(k, span_len)
+  int32_t n_split;         // workgroups per (sequence, head) in the gather launch
+  float* tmax_ws;          // [B * H][n_span] largest logit numerator of each span
+  float* zsum_ws;          // [B * H][n_span] sum over the span of exp((d - span max) / tau)
+  int32_t* cnt_ws;         // [B * H][n_span] candidates of each span
+  float* tau_ws;           // [B * H]
+  float* alpha_ws;         // [B * H]
+  uint32_t* cand_key_ws;   // [B * H][n_span][cand_cap] keys of the candidates, position-ascending
+  int32_t* cand_pos_ws;    // [B * H][n_span][cand_cap] their positions
+  int32_t* list_ws;        // [B * H][S_max] selected positions, ascending
+  float* part_ws;          // [B * H][n_split][d_h + 2] attention partials
+};
+
 struct SplitArgs {
   DecodeArgs d;
   int32_t n_split;       // workgroups per (sequence, head) in both launches
@@ -60,6 +81,12 @@ size_t decode_shared_lds_bytes(int S_max, int d_h, int g);   // 0: no grouped-qu
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s);
 size_t decode_single_k_lds_bytes(int S_max, int d_h);
 hipError_t launch_decode_single_k(const DecodeArgs& a, int dtype, hipStream_t s);
+size_t long_scores_lds_bytes(int span_len, int d_h);
+size_t long_merge_lds_bytes(int n_span, int cand_cap);
+hipError_t launch_decode_long(const LongArgs& a, int dtype, hipStream_t s);
+// the last two launches of the split-sequence plan (gather over slices of list_ws, merge): uses d, n_split,
+// alpha_ws, list_ws, part_ws of `a`
+hipError_t launch_split_gather(const SplitArgs& a, int dtype, hipStream_t s);
 hipError_t launch_decode_shared(const DecodeArgs& a, int dtype, hipStream_t s);
 hipError_t launch_decode_split(const SplitArgs& a, int dtype, hipStream_t s);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t s);

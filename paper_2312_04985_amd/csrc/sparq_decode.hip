@@ -99,7 +99,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
     if (h == 0 && tid == 0) a.seq_lens_next[b] = S;
   }
   int kb = a.k_per_seq ? a.k_per_seq[b] : a.k;
-  if (kb < 1) kb = 1;
+  kb = kb < 1 ? 1 : (kb > a.k ? a.k : kb);
   const int kq = kb < S ? kb : S;
 
   uint16_t* out = reinterpret_cast<uint16_t*>(a.out) + (size_t)u * DH;

@@ -143,7 +143,7 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
     S = S < 0 ? 0 : a.S_max;
   }
   int kb = a.k_per_seq ? a.k_per_seq[b] : a.k;
-  if (kb < 1) kb = 1;
+  kb = kb < 1 ? 1 : (kb > a.k ? a.k : kb);
   const int kq = kb < S ? kb : S;
   uint16_t* out = reinterpret_cast<uint16_t*>(a.out) + u0 * DH;
   if (S == 0) {

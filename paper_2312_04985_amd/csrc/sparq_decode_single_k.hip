@@ -111,7 +111,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_single_k(const DecodeArgs 
     S = S < 0 ? 0 : a.S_max;
   }
   int kb = a.k_per_seq ? a.k_per_seq[b] : a.k;
-  if (kb < 1) kb = 1;
+  kb = kb < 1 ? 1 : (kb > a.k ? a.k : kb);
   const int kq = kb < S ? kb : S;
   uint16_t* out = reinterpret_cast<uint16_t*>(a.out) + (size_t)u * DH;
   int32_t* idx_out = a.idx_out ? a.idx_out + (size_t)u * a.idx_stride : nullptr;

@@ -123,7 +123,7 @@ __global__ __launch_bounds__(NT) void split_select(const SplitArgs a) {
   S = S < 0 ? 0 : (S > d.S_max ? d.S_max : S);
   if (S == 0) return;                      // outputs written by split_scores
   int kb = d.k_per_seq ? d.k_per_seq[b] : d.k;
-  if (kb < 1) kb = 1;
+  kb = kb < 1 ? 1 : (kb > d.k ? d.k : kb);
   const int kq = kb < S ? kb : S;
   int32_t* idx_out = d.idx_out ? d.idx_out + (size_t)u * d.idx_stride : nullptr;
   const Window win = make_window(d.local_window, S, kq);
@@ -189,7 +189,7 @@ __global__ __launch_bounds__(NT, 4) void split_gather(const SplitArgs a) {
   S = S < 0 ? 0 : (S > d.S_max ? d.S_max : S);
   if (S == 0) return;                      // outputs written by the first launch
   int kb = d.k_per_seq ? d.k_per_seq[b] : d.k;
-  if (kb < 1) kb = 1;
+  kb = kb < 1 ? 1 : (kb > d.k ? d.k : kb);
   const int kq = kb < S ? kb : S;
 
   using G = RowGeometry<DH>;
@@ -279,7 +279,27 @@ hipError_t launch_pair(const SplitArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <class T, int DH>
+hipError_t launch_tail(const SplitArgs& a, hipStream_t s) {
+  const int units = a.d.B * a.d.H;
+  hipLaunchKernelGGL((split_gather<T, DH>), dim3(units * a.n_split), dim3(NT), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((split_combine<T, DH>), dim3(units), dim3(DH), 0, s, a);
+  return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_split_gather(const SplitArgs& a, int dtype, hipStream_t s) {
+  const bool bf = dtype == 1;
+  switch (a.d.d_h) {
+    case 64:  return bf ? launch_tail<BF16, 64>(a, s) : launch_tail<F16, 64>(a, s);
+    case 128: return bf ? launch_tail<BF16, 128>(a, s) : launch_tail<F16, 128>(a, s);
+    case 256: return bf ? launch_tail<BF16, 256>(a, s) : launch_tail<F16, 256>(a, s);
+    default:  return hipErrorInvalidValue;
+  }
+}
 
 size_t split_select_lds_bytes(int S_max) { return 4 * ((size_t)S_max + 2 * kRadixBins + 32 + 16 + 8); }
 

@@ -435,3 +435,43 @@ def test_single_copy_step_and_refusals():
     with pytest.raises(B.SparqError) as e:
         b.cache.with_params(w.r, w.k, B.SPARQ_FLAG_SINGLE_K | B.SPARQ_FLAG_GQA_SHARED).decode(q)
     assert e.value.status == B.SPARQ_EUNSUPPORTED
+
+
+# ------------------------------------------------------------------ sequences beyond one workgroup's LDS
+
+@pytest.mark.parametrize("name,kw,extra", [
+    ("long_50k", dict(B=2, H=2, H_kv=2, d_h=128, S=50001, r=32, k=512, dtype="f16"), {}),
+    ("long_131k_bf16", dict(B=1, H=4, H_kv=2, d_h=128, S=131072, r=32, k=2048, dtype="bf16"), {}),
+    ("long_d256", dict(B=1, H=2, H_kv=2, d_h=256, S=70000, r=64, k=1000, dtype="bf16"), {}),
+    ("long_d64_window", dict(B=1, H=4, H_kv=4, d_h=64, S=40961, r=16, k=128, dtype="f16"), dict(local_window=32)),
+    ("long_window_over_two_spans", dict(B=1, H=2, H_kv=2, d_h=128, S=49160, r=16, k=64, dtype="f16"), dict(local_window=40)),
+    ("long_k_over_span", dict(B=1, H=2, H_kv=1, d_h=128, S=40000, r=16, k=3000, dtype="f16"), {}),
+])
+def test_long_sequence_plan(name, kw, extra):
+    """S_max beyond ~35 000 positions: spans select their own top-k, one workgroup merges the candidates.
+    Ragged: the second sequence ends inside the first span, so later spans of it are empty."""
+    w = W.Workload(name, seed=95, **kw)
+    seq = torch.tensor([w.S if i == 0 else 5000 + 3 * i for i in range(w.B)], dtype=torch.int32)
+    st = run(w, q_scale=0.02, v_offset=True, seq_lens=seq, single_appends=3, **extra)
+    say(st)
+
+
+def test_long_sequence_step_ties_and_ragged_k():
+    """The one-call step under the long plan; duplicated keys at the threshold across span boundaries;
+    a per-sequence k."""
+    w = W.Workload("long_step", 2, 2, 2, 128, 45000, 16, 256, "f16", seed=96, k_div=200)
+    seq = torch.tensor([45000, 9000], dtype=torch.int32)
+    b = Hn.build_cache(w, v_offset=True, seq_lens=seq, S_max=45056, dup_rows=400)
+    b = Hn.Built(w, b.cache, b.K_src, b.V_src, b.seq_lens, W.k_per_seq(w, seq))
+    q = W.draw_queries(w, b.K_src, b.seq_lens, q_scale=0.02)[0]
+    say(Hn.compare_decode(b, q))
+    kn, vn = W.draw_kv(W.scaled(w, seed=97), "cuda", n_rows=1, v_offset=True)
+    out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q, b.k_per_seq.cuda())
+    torch.cuda.synchronize()
+    assert b.cache.seq_lens.cpu().tolist() == [45001, 9001] and b.cache.error_flags() == 0
+    Kg, Vg = torch.cat([b.K_src, kn], dim=2), torch.cat([b.V_src, vn], dim=2)      # room for one more row
+    for i in range(w.B):                                                            # the row lands at S_b
+        Kg[i, :, int(seq[i])] = kn[i, :, 0]; Vg[i, :, int(seq[i])] = vn[i, :, 0]
+    grown = Hn.Built(w, b.cache, Kg, Vg, b.seq_lens + 1, b.k_per_seq)
+    say(Hn.compare_decode(grown, q))
+    assert torch.equal(out.view(torch.int16), b.cache.decode(q, b.k_per_seq.cuda()).view(torch.int16))
