@@ -446,6 +446,10 @@ def test_single_copy_step_and_refusals():
     ("long_d64_window", dict(B=1, H=4, H_kv=4, d_h=64, S=40961, r=16, k=128, dtype="f16"), dict(local_window=32)),
     ("long_window_over_two_spans", dict(B=1, H=2, H_kv=2, d_h=128, S=49160, r=16, k=64, dtype="f16"), dict(local_window=40)),
     ("long_k_over_span", dict(B=1, H=2, H_kv=1, d_h=128, S=40000, r=16, k=3000, dtype="f16"), {}),
+    # few units and a long cache: the same plan with spans of 4096 although one workgroup could hold S_max
+    ("two_level_span4096", dict(B=3, H=2, H_kv=2, d_h=128, S=17000, r=16, k=300, dtype="f16"), {}),
+    ("two_level_tau_sqrt_r", dict(B=2, H=4, H_kv=1, d_h=128, S=33000, r=16, k=700, dtype="bf16"),
+     dict(flags=B.SPARQ_FLAG_TAU_SQRT_R | B.SPARQ_FLAG_NO_REALLOC)),
 ])
 def test_long_sequence_plan(name, kw, extra):
     """S_max beyond ~35 000 positions: spans select their own top-k, one workgroup merges the candidates.
