@@ -247,17 +247,24 @@ def compare_decode(b: Built, q: torch.Tensor, *, flags: int = 0, check_state: bo
 
 
 def compare_sampled(b: Built, q: torch.Tensor, *, n_units: int = 48, flags: int = 0, seed: int = 0,
-                    with_dense: bool = True) -> dict:
+                    with_dense: bool = True, step_rows=None) -> dict:
     """Full-size run on the GPU, oracle on a seeded sample of (sequence, KV head) units: only the
     sampled heads' rows travel to the host.  The sample is handed to the oracle as a batch of
     n_units sequences with one KV head and g query heads each; checks are those of compare_decode,
-    including the cache state of the sampled heads."""
+    including the cache state of the sampled heads.  With step_rows = (k_new, v_new) the GPU runs
+    sparq_decode_step instead of sparq_decode."""
     w, c = b.w, b.cache
     g = w.H // w.H_kv
     dev_k = None if b.k_per_seq is None else b.k_per_seq.to(c.device)
     kq_all = torch.minimum(b.k_per_seq if b.k_per_seq is not None else torch.full_like(b.seq_lens, w.k), b.seq_lens)
     c.with_params(w.r, w.k, flags)
-    out, alpha, idx, chan = c.decode(q, dev_k, aux=True, idx_stride=max(int(kq_all.max()), 1))
+    if step_rows is None:
+        out, alpha, idx, chan = c.decode(q, dev_k, aux=True, idx_stride=max(int(kq_all.max()), 1))
+    else:
+        # the one-launch step: `b` already describes the cache as it must be AFTER the append of step_rows
+        out, alpha, idx, chan = c.step(step_rows[0], step_rows[1], q, dev_k, aux=True, idx_stride=max(int(kq_all.max()), 1))
+        torch.cuda.synchronize()
+        assert c.seq_lens.cpu().tolist() == b.seq_lens.tolist()
     dense = c.dense(q) if with_dense else None
     torch.cuda.synchronize()
     assert c.error_flags() == 0

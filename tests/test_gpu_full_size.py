@@ -33,3 +33,27 @@ def test_full_size_sampled(name, n_units, singles):
     say("   ", stats)
     del b
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name,n_units", [("c2_llama2_7b", 48), ("c4_large_batch", 24), ("c5_gemma_7b_ragged", 16)])
+def test_full_size_one_launch_step(name, n_units):
+    """The launch the benchmark times: sparq_decode_step on the full batch, the new row landing at S_b - 1
+    of every sequence; sampled units against the oracle on the grown cache, cache state included."""
+    w = C[name]
+    seq = W.draw_seq_lens(w)                       # lengths AFTER the step
+    K_src, V_src = W.draw_kv(w, "cuda", n_rows=int(seq.max()))
+    S_max = W.round_up(int(seq.max()), 64)
+    from paper_2312_04985_amd.cache import DecodeCache
+    flags = B.SPARQ_FLAG_RAGGED_BATCH if w.ragged else 0
+    c = DecodeCache(w.B, w.H, w.H_kv, S_max, w.d_h, w.r, w.k, w.torch_dtype, flags=flags)
+    c.append(K_src, V_src, (seq - 1).cuda())       # all but the last row of every sequence
+    last = (seq - 1).to(torch.int64).cuda().view(w.B, 1, 1, 1).expand(w.B, w.H_kv, 1, w.d_h)
+    k_new = K_src.gather(2, last).squeeze(2).contiguous(); v_new = V_src.gather(2, last).squeeze(2).contiguous()
+    b = Hn.Built(w, c, K_src, V_src, seq, W.k_per_seq(w, seq))
+    q = W.draw_queries(w, K_src, seq, n=1)[0]
+    say(f"[full-size step] {name}: seq_lens {seq[:6].tolist()}")
+    stats = Hn.compare_sampled(b, q, n_units=n_units, seed=w.seed + 1, flags=flags, with_dense=False,
+                               step_rows=(k_new, v_new))
+    say("   ", stats)
+    del b, c
+    torch.cuda.empty_cache()
