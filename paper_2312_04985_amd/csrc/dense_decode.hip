@@ -115,20 +115,54 @@ __global__ __launch_bounds__(DT) void dense_partial(const DenseArgs a) {
   }
 }
 
+// Merge of the n_split partials of one (sequence, query head).  512 threads = 512 / d_h groups of d_h
+// channels; group g folds partials g, g + NG, ... online (four loads in flight per thread), the groups
+// are merged through LDS.
+constexpr int CT = 512;
+
 template <class T, int DH>
-__global__ __launch_bounds__(DH) void dense_combine(const DenseArgs a) {
-  const int u = blockIdx.x, c = threadIdx.x;
+__global__ __launch_bounds__(CT) void dense_combine(const DenseArgs a) {
+  constexpr int NG = CT / DH;
+  __shared__ float sm[NG * (DH + 2)];
+  const int u = blockIdx.x, c = threadIdx.x % DH, grp = threadIdx.x / DH;
   const float* src = a.partials + (size_t)u * a.n_split * (DH + 2);
-  float m_all = -INFINITY;
-  for (int s = 0; s < a.n_split; ++s) m_all = fmaxf(m_all, src[s * (DH + 2) + DH]);
-  float l_all = 0.0f, y = 0.0f;
-  for (int s = 0; s < a.n_split; ++s) {
-    const float w = weight_exp2(src[s * (DH + 2) + DH], m_all);
-    l_all += src[s * (DH + 2) + DH + 1] * w;
-    y += src[s * (DH + 2) + c] * w;
+  float m = -INFINITY, l = 0.0f, y = 0.0f;
+  for (int s0 = grp; s0 < a.n_split; s0 += NG * 4) {
+    float pm[4], pl[4], py[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int s = s0 + t * NG;
+      const bool on = s < a.n_split;
+      pm[t] = on ? src[s * (DH + 2) + DH] : -INFINITY;
+      pl[t] = on ? src[s * (DH + 2) + DH + 1] : 0.0f;
+      py[t] = on ? src[s * (DH + 2) + c] : 0.0f;
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const float m_new = fmaxf(m, pm[t]);
+      const float w_old = weight_exp2(m, m_new), w = weight_exp2(pm[t], m_new);
+      l = l * w_old + pl[t] * w;
+      y = y * w_old + py[t] * w;
+      m = m_new;
+    }
   }
-  uint16_t* out = reinterpret_cast<uint16_t*>(a.out) + (size_t)u * DH;
-  out[c] = l_all > 0.0f ? T::narrow(y / l_all) : (uint16_t)0;   // empty sequence: zeros
+  sm[grp * (DH + 2) + c] = y;
+  if (c == 0) { sm[grp * (DH + 2) + DH] = m; sm[grp * (DH + 2) + DH + 1] = l; }
+  __syncthreads();
+  if (grp == 0) {
+    float m_all = -INFINITY;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) m_all = fmaxf(m_all, sm[g * (DH + 2) + DH]);
+    float l_all = 0.0f, y_all = 0.0f;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const float w = weight_exp2(sm[g * (DH + 2) + DH], m_all);
+      l_all += sm[g * (DH + 2) + DH + 1] * w;
+      y_all += sm[g * (DH + 2) + c] * w;
+    }
+    uint16_t* out = reinterpret_cast<uint16_t*>(a.out) + (size_t)u * DH;
+    out[c] = l_all > 0.0f ? T::narrow(y_all / l_all) : (uint16_t)0;   // empty sequence: zeros
+  }
 }
 
 template <class T, int DH, int G>
@@ -138,7 +172,7 @@ hipError_t launch_g(const DenseArgs& a, hipStream_t s) {
   hipLaunchKernelGGL((dense_partial<T, DH, G>), dim3(blocks), dim3(DT), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((dense_combine<T, DH>), dim3(a.B * a.H), dim3(DH), 0, s, a);
+  hipLaunchKernelGGL((dense_combine<T, DH>), dim3(a.B * a.H), dim3(CT), 0, s, a);
   return hipGetLastError();
 }
 
