@@ -38,6 +38,10 @@ class DecodeCache:
         """The same buffers seen through another (r, k, flags, local window) setting."""
         self.r, self.k = r, k
         self.shape = B.make_shape(self.B, self.H, self.H_kv, self.S_max, self.d_h, r, k, self.dtype, flags, local_window)
+        need = B.sparq_workspace_bytes(self.shape)          # the plan, and with it the scratch size, may change
+        if need > self.workspace.numel():
+            self.workspace = torch.empty((need,), dtype=torch.uint8, device=self.device)
+            B.sparq_workspace_init(self.workspace)
         return self
 
     def append(self, k_new: torch.Tensor, v_new: torch.Tensor, n_new_per_seq: Optional[torch.Tensor] = None, stream=None):

@@ -179,6 +179,7 @@ size_t workspace_need(const sparq_shape* s) {
   size_t e = 0;
   if (p.plan == kPlanSplit) e = split_layout(s, p.n_split).end;
   if (p.plan == kPlanLong) e = long_layout(s, p).end;
+  if (p.plan == kPlanShared) e = (size_t)kControlBytes + (size_t)s->B * s->H * s->S_max * sizeof(float);
   return e > need ? e : need;
 }
 
@@ -208,7 +209,8 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
     d.k_new = nullptr; d.v_new = nullptr; d.v_mean_next = nullptr; d.seq_lens_next = nullptr;
   }
   if (one_k) return launch_decode_single_k(d, shape->dtype, s);
-  if (p.plan == kPlanShared) return launch_decode_shared(d, shape->dtype, s);
+  if (p.plan == kPlanShared)
+    return launch_decode_shared(d, reinterpret_cast<float*>(static_cast<char*>(workspace) + kControlBytes), shape->dtype, s);
   char* w = static_cast<char*>(workspace);
   if (p.plan == kPlanLong) {
     const LongLayout l = long_layout(shape, p);

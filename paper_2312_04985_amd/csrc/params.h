@@ -87,7 +87,8 @@ hipError_t launch_decode_long(const LongArgs& a, int dtype, hipStream_t s);
 // the last two launches of the split-sequence plan (gather over slices of list_ws, merge): uses d, n_split,
 // alpha_ws, list_ws, part_ws of `a`
 hipError_t launch_split_gather(const SplitArgs& a, int dtype, hipStream_t s);
-hipError_t launch_decode_shared(const DecodeArgs& a, int dtype, hipStream_t s);
+// z_ws: [B * H][S_max] fp32 scratch for the logit numerators
+hipError_t launch_decode_shared(const DecodeArgs& a, float* z_ws, int dtype, hipStream_t s);
 hipError_t launch_decode_split(const SplitArgs& a, int dtype, hipStream_t s);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t s);
 hipError_t launch_dense(const DenseArgs& a, int dtype, hipStream_t s);

@@ -3,14 +3,17 @@
 // |q| and ONE position set from the group sum of their approximate scores s-hat; the temperature,
 // alpha and the exact attention stay per query head.  One workgroup per (sequence, KV head).
 //   stage 0  group sums of |q| in fp64 (head order, as the definition is written), top-r, per-head tau
-//   pass A   stream the r channel rows once for all G heads: per-head max and sum-exp of the logits
-//   pass B   stream them again: score_i = sum_h softmax_h(z)_i as integer keys in LDS
+//   pass A   stream the r channel rows once for all G heads: the G logit numerators of every position go to
+//            the workspace (fp32), per-head max and sum-exp stay in registers
+//   pass B   read them back: score_i = sum_h softmax_h(z)_i as integer keys in LDS
 //   stage 2  radix select of the k largest scores, ordered position list
-//   stage 3  gather each selected K and V row once for the G heads: exact attention per head, and
-//            per-head alpha from the approximate logit recomputed on the gathered key row
+//   stage 3  gather each selected K and V row once for the G heads: exact attention per head; per-head
+//            alpha from the stored logits of the selected positions
 //   blend    y_h = alpha_h y3_h + (1 - alpha_h) v_mean (Eq. 8), round and store
-// The group sum of softmaxes is not monotone in any one head's logits, which is why the logits are
-// produced twice instead of being kept (G x S floats do not fit in LDS for long sequences).
+// The group sum of softmaxes is not monotone in any one head's logits, so the logits themselves are needed
+// twice (statistics, then scores) and a third time for alpha; G x S floats do not fit in LDS for long
+// sequences, so they live in the workspace (16 bytes per position for G = 4, against 2 r bytes for streaming
+// the key rows again), written and read by the same workgroup.
 #include "decode_stages.h"
 
 namespace sparq {
@@ -129,7 +132,7 @@ __device__ __forceinline__ void stream_channel_rows_group(const char* Kt_head, s
 }
 
 template <class T, int DH, int G>
-__global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a) {
+__global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a, float* __restrict__ z_ws) {
   extern __shared__ __align__(16) uint32_t smem[];
   const SharedLds<DH, G> L = carve_shared<DH, G>(smem, a.S_max);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -248,17 +251,19 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
   float mt[G], zt[G];   // running max of the logit numerator, sum of exp2((d - max) * esc)
 #pragma unroll
   for (int h = 0; h < G; ++h) { mt[h] = -INFINITY; zt[h] = 0.0f; }
+  float* z_unit = z_ws + u0 * (size_t)a.S_max;        // [G][S_max] logit numerators of this group
   stream_channel_rows_group<T, G>(Kt_head, row_bytes, L.chan, L.qs, DH, a.r, n_chunks, tid,
                                   [&](int c, const float (&acc)[G][8]) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      if (c * 8 + e < S) {
+    for (int h = 0; h < G; ++h) {
+      float4* dst = reinterpret_cast<float4*>(z_unit + (size_t)h * a.S_max + c * 8);
+      dst[0] = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
+      dst[1] = make_float4(acc[h][4], acc[h][5], acc[h][6], acc[h][7]);
 #pragma unroll
-        for (int h = 0; h < G; ++h) {
-          const float v = acc[h][e];
-          if (v > mt[h]) { zt[h] = zt[h] * exp2f((mt[h] - v) * esc[h]) + 1.0f; mt[h] = v; }
-          else zt[h] += exp2f((v - mt[h]) * esc[h]);
-        }
+      for (int e = 0; e < 8; ++e) {
+        const float v = acc[h][e];
+        if (v > mt[h]) { zt[h] = zt[h] * exp2f((mt[h] - v) * esc[h]) + 1.0f; mt[h] = v; }
+        else zt[h] += exp2f((v - mt[h]) * esc[h]);
       }
     }
   });
@@ -266,6 +271,7 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
 #pragma unroll
     for (int h = 0; h < G; ++h) {
       const float v = tdot[h];
+      z_unit[(size_t)h * a.S_max + S_fl + wave] = v;
       if (v > mt[h]) { zt[h] = zt[h] * exp2f((mt[h] - v) * esc[h]) + 1.0f; mt[h] = v; }
       else zt[h] += exp2f((v - mt[h]) * esc[h]);
     }
@@ -299,25 +305,30 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
   }
 
   // ---------------- pass B: group score = sum over heads of s-hat, as keys ----------------
-  stream_channel_rows_group<T, G>(Kt_head, row_bytes, L.chan, L.qs, DH, a.r, n_chunks, tid,
-                                  [&](int c, const float (&acc)[G][8]) {
+  // (the barrier above also orders this workgroup's stores of pass A before these loads)
+  for (int c = tid; c < n_chunks; c += NT) {
+    float4 lo[G], hi[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      const float4* src = reinterpret_cast<const float4*>(z_unit + (size_t)h * a.S_max + c * 8);
+      lo[h] = src[0]; hi[h] = src[1];
+    }
     uint32_t kx[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      if (c * 8 + e < S) {
-        float score = 0.0f;
+      float score = 0.0f;
 #pragma unroll
-        for (int h = 0; h < G; ++h) score += exp2f((acc[h][e] - mh[h]) * esc[h]) * inv_z[h];
-        kx[e] = float_to_key(score);
-        if (c * 8 + e < win.S_old) atomicAdd(&L.sel.hist[hist_slot(kx[e] >> 21)], 1u);
-      } else {
-        kx[e] = 0u;
+      for (int h = 0; h < G; ++h) {
+        const float v = e < 4 ? (&lo[h].x)[e] : (&hi[h].x)[e - 4];
+        score += exp2f((v - mh[h]) * esc[h]) * inv_z[h];
       }
+      kx[e] = float_to_key(score);
+      if (c * 8 + e < win.S_old) atomicAdd(&L.sel.hist[hist_slot(kx[e] >> 21)], 1u);
     }
     uint4* dst = reinterpret_cast<uint4*>(L.keys + c * 8);
     dst[0] = make_uint4(kx[0], kx[1], kx[2], kx[3]);
     dst[1] = make_uint4(kx[4], kx[5], kx[6], kx[7]);
-  });
+  }
   if (wave < n_tail && lane == 0) {
     float score = 0.0f;
 #pragma unroll
@@ -344,6 +355,17 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
         idx_out[(size_t)h * a.idx_stride + n] = n < shown ? (int)L.keys[n] : -1;
   }
 
+  // alpha_h = sum over the selected positions of s-hat_h, from the stored logits (the same values the
+  // normaliser was summed from)
+  float asum[G];
+#pragma unroll
+  for (int h = 0; h < G; ++h) asum[h] = 0.0f;
+  for (int n = tid; n < kq; n += NT) {
+    const int pos = (int)L.keys[n];
+#pragma unroll
+    for (int h = 0; h < G; ++h) asum[h] += exp2f((z_unit[(size_t)h * a.S_max + pos] - mh[h]) * esc[h]);
+  }
+
   // ---------------- stage 3: one gather for the G heads ----------------
   using Geo = RowGeometry<DH>;
   constexpr int UNR = 2, GROUP = Geo::RPI * UNR;
@@ -352,18 +374,17 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
   const char* K_head = reinterpret_cast<const char*>(a.K) + kv_head * a.S_max * (size_t)(DH * 2) + sub * 16;
   const char* V_head = reinterpret_cast<const char*>(a.V) + kv_head * a.S_max * (size_t)(DH * 2) + sub * 16;
   const float qscale = kLog2e / sqrtf((float)DH);
-  float q8[G][8], qa8[G][8];   // exact query slice (exp2 domain) and the channel-masked one over tau_h
-  float m_run[G], l_run[G], asum[G], acc[G][8];
+  float q8[G][8];   // query slices, exp2 domain
+  float m_run[G], l_run[G], acc[G][8];
 #pragma unroll
   for (int h = 0; h < G; ++h) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float qv = L.qf[h * DH + sub * 8 + e];
       q8[h][e] = qv * qscale;
-      qa8[h][e] = qv * L.selmask[sub * 8 + e] * esc[h];
       acc[h][e] = 0.0f;
     }
-    m_run[h] = -INFINITY; l_run[h] = 0.0f; asum[h] = 0.0f;
+    m_run[h] = -INFINITY; l_run[h] = 0.0f;
   }
   const int n_groups = (kq + GROUP - 1) / GROUP;
   auto issue = [&](uint4 (&kr)[UNR], uint4 (&vr)[UNR], int g) {
@@ -384,11 +405,10 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
       unpack8<T>(vr[t], vf);
 #pragma unroll
       for (int h = 0; h < G; ++h) {
-        float dot = 0.0f, adot = 0.0f;
+        float dot = 0.0f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { dot = fmaf(kf[e], q8[h][e], dot); adot = fmaf(kf[e], qa8[h][e], adot); }
+        for (int e = 0; e < 8; ++e) dot = fmaf(kf[e], q8[h][e], dot);
         dot = lanes_sum<Geo::LPR>(dot);
-        adot = lanes_sum<Geo::LPR>(adot);
         if (ok) {
           const float m_new = fmaxf(m_run[h], dot);
           const float sc = exp2f(m_run[h] - m_new), pr = exp2f(dot - m_new);
@@ -396,7 +416,6 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
 #pragma unroll
           for (int e = 0; e < 8; ++e) acc[h][e] = acc[h][e] * sc + pr * vf[e];
           m_run[h] = m_new;
-          asum[h] += exp2f(adot - mh[h] * esc[h]);      // s-hat numerator of this position for head h
         }
       }
     }
@@ -422,8 +441,7 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
   __syncthreads();   // hist and rankp are dead: `part` may overwrite them
 #pragma unroll
   for (int h = 0; h < G; ++h) {
-    // every lane of a row group holds the same s-hat terms: count them once
-    const float a_w = wave_sum(sub == 0 ? asum[h] : 0.0f);
+    const float a_w = wave_sum(asum[h]);
     if (lane == 0) L.stat[(wave * G + h) * 2] = a_w;
     store_wave_partial<DH>(m_run[h], l_run[h], acc[h], L.part + h * (DH + 2), lane, wave * G);   // part[wave][h]
   }
@@ -454,7 +472,7 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a)
 }
 
 template <class T, int DH, int G>
-hipError_t launch_shared_g(const DecodeArgs& a, hipStream_t s) {
+hipError_t launch_shared_g(const DecodeArgs& a, float* z_ws, hipStream_t s) {
   const size_t lds = 4 * ((size_t)a.S_max + shared_fixed_words<DH, G>());
   auto kern = sparq_decode_shared<T, DH, G>;
   if (lds > 64 * 1024) {
@@ -462,15 +480,15 @@ hipError_t launch_shared_g(const DecodeArgs& a, hipStream_t s) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(kern, dim3(a.B * a.H_kv), dim3(NT), lds, s, a);
+  hipLaunchKernelGGL(kern, dim3(a.B * a.H_kv), dim3(NT), lds, s, a, z_ws);
   return hipGetLastError();
 }
 
 template <class T, int DH>
-hipError_t launch_shared_dh(const DecodeArgs& a, hipStream_t s) {
+hipError_t launch_shared_dh(const DecodeArgs& a, float* z_ws, hipStream_t s) {
   switch (a.H / a.H_kv) {
-    case 2: return launch_shared_g<T, DH, 2>(a, s);
-    case 4: return launch_shared_g<T, DH, 4>(a, s);
+    case 2: return launch_shared_g<T, DH, 2>(a, z_ws, s);
+    case 4: return launch_shared_g<T, DH, 4>(a, z_ws, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -493,12 +511,12 @@ size_t decode_shared_lds_bytes(int S_max, int d_h, int g) {
   }
 }
 
-hipError_t launch_decode_shared(const DecodeArgs& a, int dtype, hipStream_t s) {
+hipError_t launch_decode_shared(const DecodeArgs& a, float* z_ws, int dtype, hipStream_t s) {
   const bool bf = dtype == 1;
   switch (a.d_h) {
-    case 64:  return bf ? launch_shared_dh<BF16, 64>(a, s) : launch_shared_dh<F16, 64>(a, s);
-    case 128: return bf ? launch_shared_dh<BF16, 128>(a, s) : launch_shared_dh<F16, 128>(a, s);
-    case 256: return bf ? launch_shared_dh<BF16, 256>(a, s) : launch_shared_dh<F16, 256>(a, s);
+    case 64:  return bf ? launch_shared_dh<BF16, 64>(a, z_ws, s) : launch_shared_dh<F16, 64>(a, z_ws, s);
+    case 128: return bf ? launch_shared_dh<BF16, 128>(a, z_ws, s) : launch_shared_dh<F16, 128>(a, z_ws, s);
+    case 256: return bf ? launch_shared_dh<BF16, 256>(a, z_ws, s) : launch_shared_dh<F16, 256>(a, z_ws, s);
     default:  return hipErrorInvalidValue;
   }
 }

@@ -230,10 +230,7 @@ def compare_decode(b: Built, q: torch.Tensor, *, flags: int = 0, check_state: bo
     ref_g = ref if stats["exact_sets"] == stats["units"] else \
         O.sparq_decode(Kh, Vh, qh, seq, r=w.r, k=w.k, dtype=w.dtype_code, flags=oflags, k_per_seq=kps, given_i2=gi)
     a_err = np.abs(alpha.cpu().numpy().astype(np.float64) - ref_g.alpha).max()
-    # The grouped-query kernel does not keep G x S logits: alpha's numerator comes from logits
-    # recomputed on the gathered key rows, the normaliser from the streamed ones.  The two fp32
-    # evaluations of one logit differ by up to 2 E, which no longer cancels in the ratio.
-    a_tol = ALPHA_TOL + (2 * stats["logit_err_bound"] if shared else 0.0)
+    a_tol = ALPHA_TOL
     assert a_err <= a_tol, f"alpha error {a_err} > {a_tol}"
     got = out.float().cpu().numpy().astype(np.float64)
     err = np.abs(got - ref_g.y)
