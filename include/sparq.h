@@ -99,10 +99,12 @@ typedef struct {
   int32_t* seq_lens; /* device */
 } sparq_cache;
 
-/* Bytes of device workspace the calls below need for this shape (>= 64 KiB).  The first 64 KiB
- * are a control block (word 0 is the error word, then arrival counters of the split-sequence
- * kernels) that sparq_workspace_init zeroes; the rest is scratch for dense_decode and for
- * sparq_decode on batches with few heads and long caches.  One workspace serves one stream. */
+/* Bytes of device workspace the calls below need for this shape (>= 64 KiB; depends on every field of
+ * the shape, flags included).  The first 64 KiB are a control block (word 0 is the error word) that
+ * sparq_workspace_init zeroes; the rest is scratch: the split-sequence partials of dense_decode, and for
+ * sparq_decode the keys / candidates / position lists of the multi-launch plans (few heads with long
+ * caches, S_max beyond one workgroup's LDS) or the logits of the grouped-query rule.  One workspace
+ * serves one stream. */
 int sparq_workspace_bytes(const sparq_shape* shape, size_t* out_bytes);
 
 /* Enqueue a clear of the control block.  Call once after allocating the workspace. */
