@@ -1,7 +1,9 @@
 // The stages of the SparQ decode step (Section 4, Steps 1-3) as workgroup-level device functions.
-// They are shared by the one-workgroup-per-head kernel (sparq_decode.hip) and by the
-// split-sequence kernels for few heads and long sequences (sparq_decode_split.hip).
-// All functions are called by all kDecodeThreads threads of a workgroup (they contain barriers).
+// Every decode plan is a different distribution of these stages over workgroups: one workgroup per
+// (sequence, head) (sparq_decode.hip), split-sequence (sparq_decode_split.hip), two-level selection
+// (sparq_decode_long.hip), the grouped-query rule (sparq_decode_shared.hip), the single-copy key cache
+// (sparq_decode_single_k.hip); the append kernels use the column flush.
+// Unless noted, functions are called by all kDecodeThreads threads of a workgroup (they contain barriers).
 #pragma once
 #include "common.h"
 #include "params.h"

@@ -29,7 +29,6 @@ struct SharedLds {
   float* qf;           // [G][DH]
   float* qs;           // [G][DH] per-head components on the shared channel list (padded, weight 0)
   int* chan;           // [DH]
-  float* selmask;      // [DH] 1 for selected channels
   double* magd;        // [DH] group sums of |q|
   float* stat;         // [NW][G][2] and [G][3]
 };
@@ -59,7 +58,6 @@ __device__ __forceinline__ SharedLds<DH, G> carve_shared(uint32_t* base, int S_m
   l.qf = reinterpret_cast<float*>(base); base += G * DH;
   l.qs = reinterpret_cast<float*>(base); base += G * DH;
   l.chan = reinterpret_cast<int*>(base); base += DH;
-  l.selmask = reinterpret_cast<float*>(base); base += DH;
   l.sel.red = reinterpret_cast<float*>(base); base += 32;
   l.sel.wcnt = base; base += 16;
   l.sel.ctl = reinterpret_cast<int*>(base); base += 8;
@@ -200,7 +198,6 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a,
       const bool sel = rank < a.r;
       const uint64_t bal = __ballot(sel);
       if (g == wave) {
-        L.selmask[jj] = sel ? 1.0f : 0.0f;
         if (sel) {
           const int p = before + __popcll(bal & ((1ull << lane) - 1ull));
           L.chan[p] = jj;
