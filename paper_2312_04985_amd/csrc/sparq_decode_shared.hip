@@ -41,7 +41,7 @@ template <int DH, int G>
 __host__ __device__ constexpr size_t shared_fixed_words() {
   size_t hist_rank = 2 * kRadixBins + NT;
   if (hist_rank < shared_part_words<DH, G>()) hist_rank = shared_part_words<DH, G>();
-  return hist_rank + 2 * (size_t)G * DH + 2 * DH + 2 * DH /* magd */ + 32 + 16 + 8 + NW * G * 2 + G * 4;
+  return hist_rank + 2 * (size_t)G * DH /* qf, qs */ + DH /* chan */ + 2 * DH /* magd */ + 32 + 16 + 8 + NW * G * 2 + G * 4;
 }
 
 template <int DH, int G>
