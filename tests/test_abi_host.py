@@ -76,6 +76,26 @@ def test_bad_pointers_and_workspace_are_refused_before_any_launch():
     assert lib.sparq_async_error(None, None, None) == B.SPARQ_EINVAL
 
 
+def test_shapes_without_a_kernel_are_refused_before_any_launch():
+    """Sizes no plan can serve, and flag combinations without a kernel, come back as SPARQ_EUNSUPPORTED
+    from the host-side planning (which assumes gfx950's 160 KiB of LDS where no device can be asked)."""
+    good = B.SparqCache(FAKE, FAKE, FAKE, FAKE, FAKE)
+    refused = [
+        dict(S_max=1 << 20, k=64),                                   # more than 64 spans of 8192
+        dict(S_max=262144, k=2048),                                  # 32 spans x 2048 candidates do not fit in LDS
+        dict(S_max=65536, flags=B.SPARQ_FLAG_GQA_SHARED),            # the grouped-query kernel is one workgroup per KV head
+        dict(S_max=65536, flags=B.SPARQ_FLAG_SINGLE_K, H=2, H_kv=2),
+        dict(H=8, H_kv=1, flags=B.SPARQ_FLAG_GQA_SHARED),            # groups of 8 query heads
+        dict(flags=B.SPARQ_FLAG_GQA_SHARED | B.SPARQ_FLAG_SINGLE_K),
+    ]
+    for kw in refused:
+        assert call_decode(shape(**kw), good) == B.SPARQ_EUNSUPPORTED, kw
+    # sizes that the two-level plan does serve still get a workspace size (and grow with S_max)
+    a = B.sparq_workspace_bytes(shape(S_max=131072, k=2048, H=2, H_kv=2))
+    b = B.sparq_workspace_bytes(shape(S_max=65536, k=2048, H=2, H_kv=2))
+    assert a > b > B.sparq_workspace_bytes(shape(S_max=8192, k=2048, H=2, H_kv=2))
+
+
 def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):
