@@ -479,3 +479,51 @@ def test_long_sequence_step_ties_and_ragged_k():
     grown = Hn.Built(w, b.cache, Kg, Vg, b.seq_lens + 1, b.k_per_seq)
     say(Hn.compare_decode(grown, q))
     assert torch.equal(out.view(torch.int16), b.cache.decode(q, b.k_per_seq.cuda()).view(torch.int16))
+
+
+# ------------------------------------------------------------------ seeded random shapes and option mixes
+
+@pytest.mark.parametrize("case", range(32))
+def test_random_shape_and_options(case):
+    """Seeded random (B, H, H_kv, d_h, S, r, k, dtype), ragged lengths, one-row appends that leave 0-7 keys
+    outside the S-contiguous copy, and a random mix of the options; every plan can come up.  One decode and
+    one one-call step per case, both against the oracle."""
+    import numpy as np
+    rng = np.random.default_rng(1000 + case)
+    d_h = int(rng.choice([64, 128, 256]))
+    H_kv = int(rng.choice([1, 2, 3]))
+    g = int(rng.choice([1, 1, 2, 4]))
+    Bn = int(rng.integers(1, 4))
+    S = int(rng.choice([rng.integers(1, 200), rng.integers(200, 3000), rng.integers(3000, 12000), rng.integers(16384, 40000)]))
+    r = int(rng.choice([8, 16, 24, 32, d_h // 2, d_h]))
+    k = int(rng.choice([1, 8, 64, 100, 512, 2048]))
+    dtype = str(rng.choice(["f16", "bf16"]))
+    flags = 0
+    if rng.random() < 0.25: flags |= B.SPARQ_FLAG_NO_REALLOC
+    if rng.random() < 0.2: flags |= int(rng.choice([B.SPARQ_FLAG_TAU_SQRT_DH, B.SPARQ_FLAG_TAU_SQRT_R]))
+    if S < 30000 and g in (2, 4) and rng.random() < 0.4: flags |= B.SPARQ_FLAG_GQA_SHARED
+    elif S < 30000 and rng.random() < 0.2: flags |= B.SPARQ_FLAG_SINGLE_K
+    window = int(rng.choice([0, 0, 1, 7, 40]))
+    singles = int(rng.integers(0, 10))
+    w = W.Workload(f"rand{case}", Bn, H_kv * g, H_kv, d_h, S, r, k, dtype, seed=2000 + case)
+    seq = torch.tensor([max(1, int(S * f)) for f in [1.0] + list(rng.uniform(0.05, 1.0, Bn - 1))], dtype=torch.int32)
+    S_max = W.round_up(S + 8, 64)
+    say(f"[random {case}] B={Bn} H={w.H}/{H_kv} d_h={d_h} S={S} r={r} k={k} {dtype} flags={flags} l={window} "
+        f"singles={singles} seq={seq.tolist()}")
+    b = Hn.build_cache(w, seq_lens=seq, S_max=S_max, v_offset=True, single_appends=singles,
+                       flags=flags & B.SPARQ_FLAG_SINGLE_K)
+    q = W.draw_queries(w, b.K_src, b.seq_lens, n=2, q_scale=float(rng.choice([1.0, 0.05, 0.01])))
+    say("   ", Hn.compare_decode(b, q[0], flags=flags, local_window=window))
+    # one step: the new row lands at S_b of every sequence
+    kn, vn = W.draw_kv(W.scaled(w, seed=3000 + case), "cuda", n_rows=1, v_offset=True)
+    b.cache.with_params(w.r, w.k, flags, window)
+    out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q[1])
+    torch.cuda.synchronize()
+    Kg, Vg = torch.cat([b.K_src, kn], dim=2), torch.cat([b.V_src, vn], dim=2)
+    for i in range(Bn):
+        Kg[i, :, int(seq[i])] = kn[i, :, 0]; Vg[i, :, int(seq[i])] = vn[i, :, 0]
+    grown = Hn.Built(w, b.cache, Kg, Vg, b.seq_lens + 1, None)
+    st = Hn.compare_decode(grown, q[1], flags=flags, local_window=window)
+    say("   ", st)
+    again = b.cache.decode(q[1])
+    assert ((out.float() - again.float()).abs() <= 2.0 ** -7 * again.float().abs() + 1e-6).all()
