@@ -140,7 +140,7 @@ int sparq_kv_append(const sparq_shape* shape, const sparq_cache* cache, const vo
  * Sizes: every plan keeps 4 bytes per position (or per candidate) of its unit of work in LDS.  One
  * workgroup per head serves S_max up to about 35 000; longer caches are selected in two levels (spans of
  * 8192 positions, at most 64 of them, ceil(S_max / 8192) * min(k, 8192) candidates <= about 36 000: e.g.
- * S_max = 524 288 at k = 512).  SPARQ_FLAG_GQA_SHARED and SPARQ_FLAG_SINGLE_K stop at about 35 000.
+ * S_max = 524 288 at k = 512), also under SPARQ_FLAG_GQA_SHARED.  SPARQ_FLAG_SINGLE_K stops at about 35 000.
  * Anything else returns SPARQ_EUNSUPPORTED before a launch.
  *   q          device [B, H, d_h]
  *   k_per_seq  device [B] or NULL; k_per_seq[b] in 1..shape.k replaces shape.k for sequence b

@@ -107,8 +107,8 @@ bool single_k(const sparq_shape* shape) { return (shape->flags & SPARQ_FLAG_SING
 
 // Which kernels serve a shape.  Every plan keeps one 4-byte key per position (or per candidate) of its
 // unit of work in LDS; that decides what fits.
-enum Plan { kPlanNone, kPlanFused, kPlanSplit, kPlanLong, kPlanShared, kPlanSingleK };
-struct PlanInfo { Plan plan; int n_split, n_span, span_len, cand_cap; };
+enum Plan { kPlanNone, kPlanFused, kPlanSplit, kPlanLong, kPlanShared, kPlanSharedSplit, kPlanSingleK };
+struct PlanInfo { Plan plan; int n_split, n_span, span_len, cand_cap, n1, span1; };
 
 // The two-level plan: spans of `span` positions select their own top-k, one workgroup per unit merges at
 // most n_span * min(k, span) candidates.  It serves what no single workgroup can hold (S_max beyond the
@@ -129,8 +129,32 @@ bool two_level_plan(const sparq_shape* s, int span, size_t lds_max, PlanInfo* p)
   return true;
 }
 
+// The grouped-query rule over several workgroups per KV unit: n1 spans for the logits (about 512 workgroups,
+// at least 1024 positions each), spans of 4096 / 8192 positions for the two-level selection.
+bool shared_split_plan(const sparq_shape* s, size_t lds_max, PlanInfo* p) {
+  const int64_t ukv = (int64_t)s->B * s->H_kv;
+  int64_t n1 = 512 / ukv;
+  if (n1 > kMaxSpans) n1 = kMaxSpans;
+  if (n1 < 1) n1 = 1;
+  int64_t span1 = (s->S_max + n1 - 1) / n1;
+  if (span1 < 1024) span1 = 1024;
+  span1 = (span1 + 63) / 64 * 64;
+  n1 = (s->S_max + span1 - 1) / span1;
+  const int span2 = s->S_max >= 32768 ? kLongSpan : kLongSpan / 2;
+  const int64_t n2 = ((int64_t)s->S_max + span2 - 1) / span2;
+  if (n1 > kMaxSpans || n2 > kMaxSpans) return false;
+  const int cap = s->k < span2 ? s->k : span2;
+  if (gs_select_lds_bytes(span2) > lds_max || gs_merge_lds_bytes((int)n2, cap) > lds_max) return false;
+  int64_t n = 512 / ukv;
+  if (n > kMaxSplit) n = kMaxSplit;
+  if (n > s->k / 64) n = s->k / 64;
+  if (n < 1) n = 1;
+  p->n1 = (int)n1; p->span1 = (int)span1; p->n_span = (int)n2; p->span_len = span2; p->cand_cap = cap; p->n_split = (int)n;
+  return true;
+}
+
 PlanInfo choose_plan(const sparq_shape* s) {
-  PlanInfo p{kPlanNone, 0, 0, 0, 0};
+  PlanInfo p{kPlanNone, 0, 0, 0, 0, 0, 0};
   const size_t lds_max = (size_t)max_lds_bytes();
   if (single_k(s)) {
     const size_t need = wants_shared(s) ? 0 : decode_single_k_lds_bytes(s->S_max, s->d_h);
@@ -139,7 +163,14 @@ PlanInfo choose_plan(const sparq_shape* s) {
   }
   if (wants_shared(s)) {
     const size_t need = decode_shared_lds_bytes(s->S_max, s->d_h, s->H / s->H_kv);
-    if (need != 0 && need <= lds_max) p.plan = kPlanShared;
+    if (need == 0) return p;                                    // no kernel for this group size
+    const bool one_wg = need <= lds_max;
+    // measured: the one-workgroup kernel is faster from about 64 KV units on (116 vs 123 us at 128 units,
+    // S = 8192) and far slower below (230 vs 70 us at 8 units, S = 32768)
+    const int64_t ukv = (int64_t)s->B * s->H_kv;
+    const bool few = (ukv <= 32 && s->S_max >= 8192) || (ukv <= 64 && s->S_max >= 16384);
+    if ((few || !one_wg) && shared_split_plan(s, lds_max, &p)) { p.plan = kPlanSharedSplit; return p; }
+    if (one_wg) p.plan = kPlanShared;
     return p;
   }
   if ((int64_t)s->B * s->H <= kSplitMaxUnits && s->S_max >= 16384) {
@@ -150,6 +181,27 @@ PlanInfo choose_plan(const sparq_shape* s) {
   if (decode_lds_bytes(s->S_max, s->d_h) <= lds_max) { p.plan = kPlanFused; return p; }
   if (two_level_plan(s, kLongSpan, lds_max, &p)) p.plan = kPlanLong;
   return p;
+}
+
+struct GsLayout { size_t z, stat, esc, alpha, cnt, ckey, cpos, list, part, end; int list_stride; };
+
+GsLayout gs_layout(const sparq_shape* s, const PlanInfo& p) {
+  const size_t units = (size_t)s->B * s->H, ukv = (size_t)s->B * s->H_kv, g = (size_t)(s->H / s->H_kv);
+  GsLayout l;
+  const int kk = s->k < s->S_max ? s->k : s->S_max;
+  l.list_stride = (kk + 7) & ~7;
+  size_t off = kControlBytes;
+  l.z = off; off = align256(off + units * s->S_max * sizeof(float));
+  l.stat = off; off = align256(off + ukv * p.n1 * g * 2 * sizeof(float));
+  l.esc = off; off = align256(off + units * sizeof(float));
+  l.alpha = off; off = align256(off + units * sizeof(float));
+  l.cnt = off; off = align256(off + ukv * p.n_span * sizeof(int32_t));
+  l.ckey = off; off = align256(off + ukv * p.n_span * p.cand_cap * sizeof(uint32_t));
+  l.cpos = off; off = align256(off + ukv * p.n_span * p.cand_cap * sizeof(int32_t));
+  l.list = off; off = align256(off + ukv * l.list_stride * sizeof(int32_t));
+  l.part = off; off = align256(off + units * p.n_split * (s->d_h + 2) * sizeof(float));
+  l.end = off;
+  return l;
 }
 
 struct LongLayout { size_t tmax, zsum, cnt, tau, alpha, ckey, cpos, list, part, end; };
@@ -180,6 +232,7 @@ size_t workspace_need(const sparq_shape* s) {
   if (p.plan == kPlanSplit) e = split_layout(s, p.n_split).end;
   if (p.plan == kPlanLong) e = long_layout(s, p).end;
   if (p.plan == kPlanShared) e = (size_t)kControlBytes + (size_t)s->B * s->H * s->S_max * sizeof(float);
+  if (p.plan == kPlanSharedSplit) e = gs_layout(s, p).end;
   return e > need ? e : need;
 }
 
@@ -212,6 +265,23 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
   if (p.plan == kPlanShared)
     return launch_decode_shared(d, reinterpret_cast<float*>(static_cast<char*>(workspace) + kControlBytes), shape->dtype, s);
   char* w = static_cast<char*>(workspace);
+  if (p.plan == kPlanSharedSplit) {
+    const GsLayout l = gs_layout(shape, p);
+    GsArgs ga;
+    ga.d = d;
+    ga.n1 = p.n1; ga.span1 = p.span1; ga.n2 = p.n_span; ga.span2 = p.span_len; ga.cand_cap = p.cand_cap;
+    ga.n_split = p.n_split; ga.list_stride = l.list_stride;
+    ga.z_ws = reinterpret_cast<float*>(w + l.z);
+    ga.stat_ws = reinterpret_cast<float*>(w + l.stat);
+    ga.esc_ws = reinterpret_cast<float*>(w + l.esc);
+    ga.alpha_ws = reinterpret_cast<float*>(w + l.alpha);
+    ga.cnt_ws = reinterpret_cast<int32_t*>(w + l.cnt);
+    ga.cand_key_ws = reinterpret_cast<uint32_t*>(w + l.ckey);
+    ga.cand_pos_ws = reinterpret_cast<int32_t*>(w + l.cpos);
+    ga.list_ws = reinterpret_cast<int32_t*>(w + l.list);
+    ga.part_ws = reinterpret_cast<float*>(w + l.part);
+    return launch_decode_shared_split(ga, shape->dtype, s);
+  }
   if (p.plan == kPlanLong) {
     const LongLayout l = long_layout(shape, p);
     LongArgs la;

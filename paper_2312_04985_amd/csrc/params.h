@@ -62,6 +62,25 @@ struct LongArgs {
   float* part_ws;          // [B * H][n_split][d_h + 2] attention partials
 };
 
+// grouped-query rule over several workgroups per (sequence, KV head)
+struct GsArgs {
+  DecodeArgs d;
+  int32_t n1, span1;       // logit spans per KV unit and their length (positions)
+  int32_t n2, span2;       // selection spans per KV unit and their length
+  int32_t cand_cap;        // candidates one selection span may hand on = min(k, span2)
+  int32_t n_split;         // gather workgroups per KV unit
+  int32_t list_stride;     // entries of one KV unit's position list
+  float* z_ws;             // [B * H][S_max] logit numerators
+  float* stat_ws;          // [B * H_kv][n1][G][2] span maximum and sum-exp per head
+  float* esc_ws;           // [B * H] log2(e) / tau
+  float* alpha_ws;         // [B * H]
+  int32_t* cnt_ws;         // [B * H_kv][n2]
+  uint32_t* cand_key_ws;   // [B * H_kv][n2][cand_cap]
+  int32_t* cand_pos_ws;    // [B * H_kv][n2][cand_cap]
+  int32_t* list_ws;        // [B * H_kv][list_stride] selected positions, ascending
+  float* part_ws;          // [B * H][n_split][d_h + 2] attention partials
+};
+
 struct SplitArgs {
   DecodeArgs d;
   int32_t n_split;       // workgroups per (sequence, head) in both launches
@@ -87,6 +106,11 @@ hipError_t launch_decode_long(const LongArgs& a, int dtype, hipStream_t s);
 // the last two launches of the split-sequence plan (gather over slices of list_ws, merge): uses d, n_split,
 // alpha_ws, list_ws, part_ws of `a`
 hipError_t launch_split_gather(const SplitArgs& a, int dtype, hipStream_t s);
+// the last launch alone: uses d, n_split, alpha_ws, part_ws
+hipError_t launch_split_combine(const SplitArgs& a, int dtype, hipStream_t s);
+size_t gs_select_lds_bytes(int span2);
+size_t gs_merge_lds_bytes(int n2, int cand_cap);
+hipError_t launch_decode_shared_split(const GsArgs& a, int dtype, hipStream_t s);
 // z_ws: [B * H][S_max] fp32 scratch for the logit numerators
 hipError_t launch_decode_shared(const DecodeArgs& a, float* z_ws, int dtype, hipStream_t s);
 hipError_t launch_decode_split(const SplitArgs& a, int dtype, hipStream_t s);

@@ -14,7 +14,7 @@
 // twice (statistics, then scores) and a third time for alpha; G x S floats do not fit in LDS for long
 // sequences, so they live in the workspace (16 bytes per position for G = 4, against 2 r bytes for streaming
 // the key rows again), written and read by the same workgroup.
-#include "decode_stages.h"
+#include "group_stages.h"
 
 namespace sparq {
 
@@ -65,70 +65,6 @@ __device__ __forceinline__ SharedLds<DH, G> carve_shared(uint32_t* base, int S_m
   return l;
 }
 
-// Step 1b for G heads at once: like stream_channel_rows, every loaded 16-byte chunk feeds G accumulators.
-template <class T, int G, class Finish>
-__device__ __forceinline__ void stream_channel_rows_group(const char* Kt_head, size_t row_bytes, const int* chan,
-                                                          const float* qs, int qs_stride, int r, int n_chunks,
-                                                          int tid, Finish&& finish) {
-  const int n_batches = (r + 7) >> 3;
-  const int my_chunks = n_chunks > tid ? (n_chunks - tid + NT - 1) / NT : 0;
-  const int items = my_chunks * n_batches;
-  float acc[G][8];
-#pragma unroll
-  for (int h = 0; h < G; ++h)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
-  int ic = 0, ib = 0, cc = 0, cb = 0;
-  auto issue_next = [&](uint4 (&v)[8]) {
-    const uint32_t voff = (uint32_t)(tid + ic * NT) * 16u;
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const int ch = __builtin_amdgcn_readfirstlane(chan[ib * 8 + t]);
-      v[t] = load16(Kt_head + (size_t)ch * row_bytes + voff);
-    }
-    if (++ib == n_batches) { ib = 0; ++ic; }
-  };
-  auto consume_next = [&](const uint4 (&v)[8]) {
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      float f[8];
-      unpack8<T>(v[t], f);
-#pragma unroll
-      for (int h = 0; h < G; ++h) {
-        const float qv = qs[h * qs_stride + cb * 8 + t];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[h][e] = fmaf(f[e], qv, acc[h][e]);
-      }
-    }
-    if (++cb == n_batches) {
-      finish(tid + cc * NT, acc);
-#pragma unroll
-      for (int h = 0; h < G; ++h)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
-      cb = 0; ++cc;
-    }
-  };
-  uint4 va[8], vb[8];
-  if (items > 0) {
-    issue_next(va);
-    int i = 0;
-    for (; i + 2 < items; i += 2) {
-      issue_next(vb);
-      consume_next(va);
-      issue_next(va);
-      consume_next(vb);
-    }
-    if (i + 1 < items) {
-      issue_next(vb);
-      consume_next(va);
-      consume_next(vb);
-    } else {
-      consume_next(va);
-    }
-  }
-}
-
 template <class T, int DH, int G>
 __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a, float* __restrict__ z_ws) {
   extern __shared__ __align__(16) uint32_t smem[];
@@ -158,74 +94,9 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a,
 
   // ---------------- stage 0: shared channel set, per-head temperature ----------------
   for (int i = tid; i < 2 * kRadixBins; i += NT) L.sel.hist[i] = 0u;
-  for (int i = tid; i < G * DH; i += NT)
-    L.qf[i] = T::widen(reinterpret_cast<const uint16_t*>(a.q)[u0 * DH + i]);
-  __syncthreads();
-  if (tid < DH) {
-    double m = 0.0;
-#pragma unroll
-    for (int h = 0; h < G; ++h) m += (double)fabsf(L.qf[h * DH + tid]);   // head order, as in the definition
-    L.magd[tid] = m;
-  }
-  __syncthreads();
-  {
-    constexpr int SL = NT / DH, PER = DH / SL;
-    const int j = tid % DH, slice = tid / DH;
-    const double mine = L.magd[j];
-    int partial = 0;
-#pragma unroll 4
-    for (int i = slice * PER; i < (slice + 1) * PER; ++i) {
-      const double m = L.magd[i];
-      partial += (m > mine) || (m == mine && i < j);
-    }
-    L.rankp[slice * DH + j] = partial;
-  }
-  __syncthreads();
   float esc[G];        // log2(e) / tau_h
-  {
-    constexpr int SL = NT / DH, NG = DH / kWave;
-    const int r8 = (a.r + 7) & ~7;
-    int before = 0;
-    float l1a[G], l1s[G];
-#pragma unroll
-    for (int h = 0; h < G; ++h) { l1a[h] = 0.0f; l1s[h] = 0.0f; }
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      const int jj = g * kWave + lane;
-      int rank = 0;
-#pragma unroll
-      for (int s = 0; s < SL; ++s) rank += L.rankp[s * DH + jj];
-      const bool sel = rank < a.r;
-      const uint64_t bal = __ballot(sel);
-      if (g == wave) {
-        if (sel) {
-          const int p = before + __popcll(bal & ((1ull << lane) - 1ull));
-          L.chan[p] = jj;
-#pragma unroll
-          for (int h = 0; h < G; ++h) L.qs[h * DH + p] = L.qf[h * DH + jj];
-          if (p == a.r - 1)
-            for (int pp = a.r; pp < r8; ++pp) {
-              L.chan[pp] = jj;
-#pragma unroll
-              for (int h = 0; h < G; ++h) L.qs[h * DH + pp] = 0.0f;
-            }
-        }
-      }
-      before += __popcll(bal);
-#pragma unroll
-      for (int h = 0; h < G; ++h) {
-        const float aq = fabsf(L.qf[h * DH + jj]);
-        l1a[h] += aq; l1s[h] += sel ? aq : 0.0f;
-      }
-    }
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const float all = wave_sum(l1a[h]), part = wave_sum(l1s[h]);
-      const float tau = part > 0.0f ? sqrtf((float)DH * part / all) : sqrtf((float)DH);   // all logits 0 then
-      esc[h] = kLog2e / apply_tau_mode(tau, a.flags, DH, a.r);
-    }
-  }
-  __syncthreads();
+  const GroupQueryLds GQ{L.rankp, L.qf, L.qs, L.chan, L.magd};
+  select_channels_group<T, DH, G>(GQ, reinterpret_cast<const uint16_t*>(a.q) + u0 * DH, a.r, a.flags, tid, lane, wave, esc);
   if (a.chan_out)
     for (int i = tid; i < G * a.r; i += NT) a.chan_out[u0 * a.r + i] = L.chan[i % a.r];
 
@@ -249,7 +120,7 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a,
 #pragma unroll
   for (int h = 0; h < G; ++h) { mt[h] = -INFINITY; zt[h] = 0.0f; }
   float* z_unit = z_ws + u0 * (size_t)a.S_max;        // [G][S_max] logit numerators of this group
-  stream_channel_rows_group<T, G>(Kt_head, row_bytes, L.chan, L.qs, DH, a.r, n_chunks, tid,
+  stream_channel_rows_group<T, G>(Kt_head, row_bytes, L.chan, L.qs, DH, a.r, 0, n_chunks, tid,
                                   [&](int c, const float (&acc)[G][8]) {
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -313,13 +184,10 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a,
     uint32_t kx[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      float score = 0.0f;
+      float dv[G];
 #pragma unroll
-      for (int h = 0; h < G; ++h) {
-        const float v = e < 4 ? (&lo[h].x)[e] : (&hi[h].x)[e - 4];
-        score += exp2f((v - mh[h]) * esc[h]) * inv_z[h];
-      }
-      kx[e] = float_to_key(score);
+      for (int h = 0; h < G; ++h) dv[h] = e < 4 ? (&lo[h].x)[e] : (&hi[h].x)[e - 4];
+      kx[e] = float_to_key(group_score<G>(dv, mh, esc, inv_z));
       if (c * 8 + e < win.S_old) atomicAdd(&L.sel.hist[hist_slot(kx[e] >> 21)], 1u);
     }
     uint4* dst = reinterpret_cast<uint4*>(L.keys + c * 8);
@@ -327,10 +195,7 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a,
     dst[1] = make_uint4(kx[4], kx[5], kx[6], kx[7]);
   }
   if (wave < n_tail && lane == 0) {
-    float score = 0.0f;
-#pragma unroll
-    for (int h = 0; h < G; ++h) score += exp2f((tdot[h] - mh[h]) * esc[h]) * inv_z[h];
-    const uint32_t key = float_to_key(score);
+    const uint32_t key = float_to_key(group_score<G>(tdot, mh, esc, inv_z));
     L.keys[S_fl + wave] = key;
     if (S_fl + wave < win.S_old) atomicAdd(&L.sel.hist[hist_slot(key >> 21)], 1u);
   }

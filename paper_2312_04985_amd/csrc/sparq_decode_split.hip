@@ -291,6 +291,22 @@ hipError_t launch_tail(const SplitArgs& a, hipStream_t s) {
 
 }  // namespace
 
+template <class T, int DH>
+hipError_t launch_combine_only(const SplitArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL((split_combine<T, DH>), dim3(a.d.B * a.d.H), dim3(DH), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_split_combine(const SplitArgs& a, int dtype, hipStream_t s) {
+  const bool bf = dtype == 1;
+  switch (a.d.d_h) {
+    case 64:  return bf ? launch_combine_only<BF16, 64>(a, s) : launch_combine_only<F16, 64>(a, s);
+    case 128: return bf ? launch_combine_only<BF16, 128>(a, s) : launch_combine_only<F16, 128>(a, s);
+    case 256: return bf ? launch_combine_only<BF16, 256>(a, s) : launch_combine_only<F16, 256>(a, s);
+    default:  return hipErrorInvalidValue;
+  }
+}
+
 hipError_t launch_split_gather(const SplitArgs& a, int dtype, hipStream_t s) {
   const bool bf = dtype == 1;
   switch (a.d.d_h) {

@@ -83,7 +83,7 @@ def test_shapes_without_a_kernel_are_refused_before_any_launch():
     refused = [
         dict(S_max=1 << 20, k=64),                                   # more than 64 spans of 8192
         dict(S_max=262144, k=2048),                                  # 32 spans x 2048 candidates do not fit in LDS
-        dict(S_max=65536, flags=B.SPARQ_FLAG_GQA_SHARED),            # the grouped-query kernel is one workgroup per KV head
+        dict(S_max=262144, k=2048, flags=B.SPARQ_FLAG_GQA_SHARED),   # the same limit under the grouped-query rule
         dict(S_max=65536, flags=B.SPARQ_FLAG_SINGLE_K, H=2, H_kv=2),
         dict(H=8, H_kv=1, flags=B.SPARQ_FLAG_GQA_SHARED),            # groups of 8 query heads
         dict(flags=B.SPARQ_FLAG_GQA_SHARED | B.SPARQ_FLAG_SINGLE_K),

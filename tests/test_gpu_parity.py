@@ -209,6 +209,11 @@ def test_unsupported_requests_are_refused():
     ("g2_bf16_d256", dict(B=2, H=4, H_kv=2, d_h=256, S=1500, r=64, k=100, dtype="bf16"), 0.003),
     ("g4_planted_long", dict(B=1, H=8, H_kv=2, d_h=128, S=20000, r=32, k=1024, dtype="bf16"), 1.0),
     ("g4_short_d64", dict(B=3, H=4, H_kv=1, d_h=64, S=70, r=8, k=100, dtype="f16"), 0.05),
+    # several workgroups per KV head (few KV heads, long caches; beyond one workgroup's LDS)
+    ("g4_split_9k", dict(B=2, H=8, H_kv=2, d_h=128, S=9001, r=16, k=300, dtype="f16"), 0.02),
+    ("g2_split_40k_d256", dict(B=1, H=4, H_kv=2, d_h=256, S=40003, r=64, k=1024, dtype="bf16"), 0.005),
+    ("g4_split_70k", dict(B=1, H=4, H_kv=1, d_h=128, S=70000, r=32, k=2048, dtype="bf16"), 0.02),
+    ("g2_split_d64", dict(B=3, H=2, H_kv=1, d_h=64, S=17000, r=8, k=64, dtype="f16"), 0.05),
 ])
 def test_grouped_query_shared_selection(name, kw, qs):
     """SPARQ_FLAG_GQA_SHARED: one channel set and one position set per KV head from the group sums
