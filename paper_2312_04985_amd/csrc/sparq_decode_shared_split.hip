@@ -283,10 +283,21 @@ __global__ __launch_bounds__(NT) void gs_merge(const GsArgs a) {
   for (int s = 0; s < a.n2; ++s) {
     const int o = off[s], cnt = off[s + 1] - o;
     const uint32_t* src = a.cand_key_ws + ((size_t)ukv * a.n2 + s) * a.cand_cap;
-    for (int n = tid; n < cnt; n += NT) {
-      const uint32_t key = src[n];
-      keys[o + n] = key;
-      if (o + n < n_free) atomicAdd(&hist[hist_slot(key >> 21)], 1u);
+    for (int n0 = 0; n0 < cnt; n0 += 4 * NT) {      // four loads in flight per thread
+      uint32_t key[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int n = n0 + t * NT + tid;
+        key[t] = n < cnt ? src[n] : 0u;
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int n = n0 + t * NT + tid;
+        if (n < cnt) {
+          keys[o + n] = key[t];
+          if (o + n < n_free) atomicAdd(&hist[hist_slot(key[t] >> 21)], 1u);
+        }
+      }
     }
   }
   __syncthreads();
