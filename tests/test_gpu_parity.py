@@ -532,3 +532,24 @@ def test_random_shape_and_options(case):
     say("   ", st)
     again = b.cache.decode(q[1])
     assert ((out.float() - again.float()).abs() <= 2.0 ** -7 * again.float().abs() + 1e-6).all()
+
+
+# ------------------------------------------------------------------ the plain streaming probes
+
+@pytest.mark.parametrize("n_bytes", [16, 4096 * 16 + 48, (1 << 26) + 16 * 12345])
+def test_probes_touch_every_byte_once(n_bytes):
+    """sparq_copy_probe copies exactly n bytes; sparq_read_probe folds every 16-byte word exactly once (the
+    xor of all per-thread results equals the xor of all 32-bit words of the buffer)."""
+    g = torch.Generator(device="cuda"); g.manual_seed(7)
+    src = torch.randint(0, 256, (n_bytes + 64,), dtype=torch.uint8, device="cuda", generator=g)
+    dst = torch.zeros_like(src)
+    B.sparq_copy_probe(dst, src, n_bytes)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n_bytes], src[:n_bytes]) and not dst[n_bytes:].any()
+    sink = torch.zeros(2 << 20, dtype=torch.uint8, device="cuda")
+    B.sparq_read_probe(src, n_bytes, sink)
+    torch.cuda.synchronize()
+    import numpy as np
+    got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
+    want = np.bitwise_xor.reduce(src[:n_bytes].cpu().numpy().view(np.uint32))
+    assert got == want
