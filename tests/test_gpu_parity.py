@@ -512,11 +512,14 @@ def test_random_shape_and_options(case):
     elif S < 30000 and rng.random() < 0.2: flags |= B.SPARQ_FLAG_SINGLE_K
     window = int(rng.choice([0, 0, 1, 7, 40]))
     singles = int(rng.integers(0, 10))
-    w = W.Workload(f"rand{case}", Bn, H_kv * g, H_kv, d_h, S, r, k, dtype, seed=2000 + case)
+    k_div = [None, None, None, 8, 50][int(rng.integers(0, 5))]       # a per-sequence k = ceil(S_b / k_div) in some cases
+    if k_div is not None:
+        k = max(k, -(-S // k_div))                                  # shape.k is the maximum
+    w = W.Workload(f"rand{case}", Bn, H_kv * g, H_kv, d_h, S, r, k, dtype, seed=2000 + case, k_div=k_div)
     seq = torch.tensor([max(1, int(S * f)) for f in [1.0] + list(rng.uniform(0.05, 1.0, Bn - 1))], dtype=torch.int32)
     S_max = W.round_up(S + 8, 64)
     say(f"[random {case}] B={Bn} H={w.H}/{H_kv} d_h={d_h} S={S} r={r} k={k} {dtype} flags={flags} l={window} "
-        f"singles={singles} seq={seq.tolist()}")
+        f"singles={singles} k_div={k_div} seq={seq.tolist()}")
     b = Hn.build_cache(w, seq_lens=seq, S_max=S_max, v_offset=True, single_appends=singles,
                        flags=flags & B.SPARQ_FLAG_SINGLE_K)
     q = W.draw_queries(w, b.K_src, b.seq_lens, n=2, q_scale=float(rng.choice([1.0, 0.05, 0.01])))
@@ -524,15 +527,16 @@ def test_random_shape_and_options(case):
     # one step: the new row lands at S_b of every sequence
     kn, vn = W.draw_kv(W.scaled(w, seed=3000 + case), "cuda", n_rows=1, v_offset=True)
     b.cache.with_params(w.r, w.k, flags, window)
-    out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q[1])
+    kps_dev = None if b.k_per_seq is None else b.k_per_seq.cuda()
+    out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q[1], kps_dev)
     torch.cuda.synchronize()
     Kg, Vg = torch.cat([b.K_src, kn], dim=2), torch.cat([b.V_src, vn], dim=2)
     for i in range(Bn):
         Kg[i, :, int(seq[i])] = kn[i, :, 0]; Vg[i, :, int(seq[i])] = vn[i, :, 0]
-    grown = Hn.Built(w, b.cache, Kg, Vg, b.seq_lens + 1, None)
+    grown = Hn.Built(w, b.cache, Kg, Vg, b.seq_lens + 1, b.k_per_seq)
     st = Hn.compare_decode(grown, q[1], flags=flags, local_window=window)
     say("   ", st)
-    again = b.cache.decode(q[1])
+    again = b.cache.decode(q[1], kps_dev)
     assert ((out.float() - again.float()).abs() <= 2.0 ** -7 * again.float().abs() + 1e-6).all()
 
 
@@ -555,3 +559,23 @@ def test_probes_touch_every_byte_once(n_bytes):
     got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
     want = np.bitwise_xor.reduce(src[:n_bytes].cpu().numpy().view(np.uint32))
     assert got == want
+
+
+def test_bulk_append_after_single_appends_completes_the_key_copy():
+    """A bulk append onto a sequence whose newest keys are not in the S-contiguous copy yet (S_b mod 8 != 0)
+    must bring those columns in as well: afterwards Kt is complete below 8 floor(S_b / 8) and the decode
+    agrees with the oracle."""
+    w = W.Workload("bulk_after_single", 2, 4, 2, 128, 165, 16, 32, "f16", seed=24)
+    K_src, V_src = W.draw_kv(w, "cuda", n_rows=165, v_offset=True)
+    c = DecodeCache(2, 4, 2, 192, 128, 16, 32, w.torch_dtype, poison=6.0e4)
+    c.append(K_src[:, :, :100].contiguous(), V_src[:, :, :100].contiguous())
+    for t in range(100, 105):                                   # S_b = 105: five keys outside the copy
+        c.append(K_src[:, :, t].contiguous(), V_src[:, :, t].contiguous())
+    n_new = torch.tensor([60, 37], dtype=torch.int32, device="cuda")     # ragged bulk: S_b = 165, 142
+    c.append(K_src[:, :, 105:165].contiguous(), V_src[:, :, 105:165].contiguous(), n_new)
+    torch.cuda.synchronize()
+    seq = torch.tensor([165, 142], dtype=torch.int32)
+    b = Hn.Built(w, c, K_src, V_src, seq, None)
+    Hn.check_cache_state(b)
+    q = W.draw_queries(w, K_src, seq, q_scale=0.02)[0]
+    say(Hn.compare_decode(b, q))
