@@ -12,6 +12,7 @@ namespace sparq {
 
 constexpr int NT = kDecodeThreads;
 constexpr int NW = NT / kWave;   // waves per workgroup
+constexpr int kTieHeavy = 2048;  // a radix bin with more keys than this is counted tie-robustly in the next pass
 
 // ------------------------------------------------------------------------------------------------
 // small workgroup primitives
@@ -19,6 +20,40 @@ constexpr int NW = NT / kWave;   // waves per workgroup
 // Histogram bins are stored swizzled so that the 32 consecutive digits a lane sums in
 // find_threshold_bin sit in 32 different rows of 64 words: lane-consecutive, conflict-free reads.
 __device__ __forceinline__ uint32_t hist_slot(uint32_t digit) { return ((digit & 31u) << 6) | (digit >> 5); }
+
+// First-digit counts of the 8 keys of one chunk: runs of equal digits among neighbours (duplicated keys) are
+// added with one atomic.  n_valid = how many of the 8 keys count (the leading ones).
+__device__ __forceinline__ void hist_add_chunk(uint32_t* hist, const uint32_t (&kx)[8], int n_valid) {
+  uint32_t run_d = kx[0] >> 21, run_n = n_valid > 0 ? 1u : 0u;
+#pragma unroll
+  for (int e = 1; e < 8; ++e) {
+    const uint32_t d = kx[e] >> 21;
+    const uint32_t v = e < n_valid ? 1u : 0u;
+    if (d != run_d) {
+      if (run_n) atomicAdd(&hist[hist_slot(run_d)], run_n);
+      run_d = d; run_n = 0u;
+    }
+    run_n += v;
+  }
+  if (run_n) atomicAdd(&hist[hist_slot(run_d)], run_n);
+}
+
+// Count one key per lane into a histogram when many lanes may hold the same digit (exact ties: 64 LDS
+// atomics on one address are serialised).  Up to four rounds: the first pending lane's digit is broadcast and
+// all lanes holding it are counted with one atomic; what is left goes through plain atomics.  Called by all
+// lanes of a wave together; lanes with valid = false contribute nothing.
+__device__ __forceinline__ void hist_add_ties(uint32_t* hist, uint32_t digit, bool valid, int lane) {
+  uint64_t todo = __ballot(valid);
+#pragma unroll 1
+  for (int it = 0; it < 4 && todo; ++it) {
+    const int leader = __ffsll((unsigned long long)todo) - 1;
+    const uint32_t dsel = (uint32_t)__builtin_amdgcn_readlane((int)digit, leader);
+    const uint64_t same = __ballot(valid && digit == dsel) & todo;
+    if (lane == leader) atomicAdd(&hist[hist_slot(dsel)], (uint32_t)__popcll(same));
+    todo &= ~same;
+  }
+  if ((todo >> lane) & 1ull) atomicAdd(&hist[hist_slot(digit)], 1u);
+}
 
 // One wave locates the digit at which the count taken from the top digit downwards reaches `need`;
 // writes {digit, how many keys of that digit are needed, keys with that digit} to ctl[0..2].
@@ -263,6 +298,7 @@ __device__ __forceinline__ void radix_select(const uint32_t* keys, int S, int kq
   const int n_chunks = (S + 7) >> 3;
   if (kq == 0) { pmask = 0xffffffffu; pval = 0xffffffffu; need = 0; return; }
   pmask = 0u; pval = 0u; need = kq;
+  int in_bin = 0;          // keys in the bin decided by the previous pass
   for (int pass = 0; pass < 3; ++pass) {
     const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
     const uint32_t dmask = pass == 2 ? 0x3ffu : 0x7ffu;
@@ -270,13 +306,28 @@ __device__ __forceinline__ void radix_select(const uint32_t* keys, int S, int kq
     if (pass > 0) {
       uint32_t* other = sl.hist + ((pass + 1) & 1) * kRadixBins;   // free since the last barrier
       for (int i = tid; i < kRadixBins; i += NT) other[i] = 0u;
-      for (int c = tid; c < n_chunks; c += NT) {
-        const uint4* src = reinterpret_cast<const uint4*>(keys + c * 8);
-        const uint4 lo = src[0], hi = src[1];
-        const uint32_t kx[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      if (in_bin <= kTieHeavy) {
+        for (int c = tid; c < n_chunks; c += NT) {
+          const uint4* src = reinterpret_cast<const uint4*>(keys + c * 8);
+          const uint4 lo = src[0], hi = src[1];
+          const uint32_t kx[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-          if (c * 8 + e < S && (kx[e] & pmask) == pval) atomicAdd(&hist[hist_slot((kx[e] >> shift) & dmask)], 1u);
+          for (int e = 0; e < 8; ++e)
+            if (c * 8 + e < S && (kx[e] & pmask) == pval) atomicAdd(&hist[hist_slot((kx[e] >> shift) & dmask)], 1u);
+        }
+      } else {
+        // thousands of keys share the decided bits (duplicated keys, underflowed scores): they may share the next
+        // digit too, and plain atomics on one address would take microseconds; count per wave first
+        for (int c0 = 0; c0 < n_chunks; c0 += NT) {
+          const int c = c0 + tid;
+          const bool on = c < n_chunks;
+          const uint4* src = reinterpret_cast<const uint4*>(keys + (on ? c : 0) * 8);
+          const uint4 lo = src[0], hi = src[1];
+          const uint32_t kx[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            hist_add_ties(hist, (kx[e] >> shift) & dmask, on && c * 8 + e < S && (kx[e] & pmask) == pval, lane);
+        }
       }
       __syncthreads();
     }
@@ -285,7 +336,7 @@ __device__ __forceinline__ void radix_select(const uint32_t* keys, int S, int kq
     pval |= (uint32_t)sl.ctl[0] << shift;
     pmask |= dmask << shift;
     need = sl.ctl[1];
-    const int in_bin = sl.ctl[2];
+    in_bin = sl.ctl[2];
     if (need == in_bin) break;   // every key matching the decided bits is taken: no ties to split
   }
 }

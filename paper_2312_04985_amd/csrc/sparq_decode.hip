@@ -143,8 +143,8 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
     for (int e = 0; e < 8; ++e) {
       tmax = fmaxf(tmax, acc[e]);
       kx[e] = float_to_key(acc[e]);
-      if (c * 8 + e < win.S_old) atomicAdd(&L.sel.hist[hist_slot(kx[e] >> 21)], 1u);
     }
+    hist_add_chunk(L.sel.hist, kx, win.S_old - c * 8);
     uint4* dst = reinterpret_cast<uint4*>(L.keys + c * 8);
     dst[0] = make_uint4(kx[0], kx[1], kx[2], kx[3]);
     dst[1] = make_uint4(kx[4], kx[5], kx[6], kx[7]);

@@ -153,9 +153,7 @@ __global__ __launch_bounds__(NT) void split_select(const SplitArgs a) {
         reinterpret_cast<uint4*>(keys + c * 8)[0] = lo[t];
         reinterpret_cast<uint4*>(keys + c * 8)[1] = hi[t];
         const uint32_t kx[8] = {lo[t].x, lo[t].y, lo[t].z, lo[t].w, hi[t].x, hi[t].y, hi[t].z, hi[t].w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          if (c * 8 + e < win.S_old) atomicAdd(&hist[hist_slot(kx[e] >> 21)], 1u);
+        hist_add_chunk(hist, kx, win.S_old - c * 8);
       }
     }
   }
