@@ -10,6 +10,11 @@
  * Notation follows the paper: B sequences, H query heads, H_kv key/value heads
  * (g = H / H_kv query heads share a KV head), head dimension d_h, S_b cached rows in
  * sequence b, r query components kept in Step 1, k positions kept in Step 2.
+ * Equation numbers are the paper's own, counting every displayed equation from its start:
+ * (1) attention's share of the data transfers (Section 2); in Section 3 (2) dense attention,
+ * (3) M_dense, (4) the exact scores s, (5) top-k sparse values, (6) mean value reallocation,
+ * (7) the approximate scores s-hat, (8) attention over the selected positions, (9) the
+ * temperature tau, (10) the blend with the mean value vector; (11) M_SparQ (Section 4).
  *
  * Cache layout (Section 6 and Appendix F, "Storing K twice": the key cache is kept in
  * both a d_h-contiguous and an S-contiguous layout so that either axis can be
@@ -26,7 +31,11 @@
  * 8 * floor(S_b / 8) equal K transposed; the up to 7 newest keys reach it when the eighth
  * arrives (one aligned 16-byte store per channel row instead of eight scattered 2-byte
  * stores) and until then Step 1 takes them from the rows of K.  Columns from
- * 8 * floor(S_b / 8) on are unspecified.
+ * 8 * floor(S_b / 8) on are unspecified.  A caller that fills or edits a cache by itself
+ * (instead of through sparq_kv_append / sparq_decode_step) has to write both layouts for all
+ * columns below 8 * floor(S_b / 8), K for all rows below S_b, and v_mean; a cache with
+ * seq_lens[b] = 0 needs no initialisation of K, Kt, V or v_mean[b] (the first append ignores
+ * whatever v_mean holds), only seq_lens must be set.
  */
 #ifndef SPARQ_H
 #define SPARQ_H
@@ -59,10 +68,11 @@ enum {
    * every query head selects independently over its shared KV head. */
   SPARQ_FLAG_GQA_SHARED = 1u << 1,
   /* scheduling hint, no effect on results: the sequence lengths of the batch differ widely;
-   * sparq_decode / sparq_decode_step then start the longest sequences first */
+   * sparq_decode / sparq_decode_step then start the longest sequences first.  Honoured by the
+   * one-workgroup-per-head plan for 2 <= B <= 512 and H = H_kv; ignored otherwise */
   SPARQ_FLAG_RAGGED_BATCH = 1u << 2,
   /* the fixed temperatures of the paper's ablation (Section 5.3, "Approximate softmax
-   * temperature") in place of Eq. (7): tau = sqrt(d_h), or tau = sqrt(r).  At most one of the two. */
+   * temperature") in place of Eq. (9): tau = sqrt(d_h), or tau = sqrt(r).  At most one of the two. */
   SPARQ_FLAG_TAU_SQRT_DH = 1u << 3,
   SPARQ_FLAG_TAU_SQRT_R = 1u << 4,
   /* the key cache is stored once, d_h-contiguous only (the "1 x K" variant of Section 6.1): cache.Kt
@@ -118,9 +128,10 @@ int sparq_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stre
  *   n_new          rows per sequence in k_new / v_new (>= 1)
  *   n_new_per_seq  device [B] or NULL: sequence b appends only its first
  *                  n_new_per_seq[b] rows (0..n_new); NULL appends n_new everywhere
- * For sequence b with n rows: rows land at positions S_b..S_b+n-1 of K and V, Kt is brought
- * up to date to column 8 * floor((S_b+n) / 8) at least, v_mean becomes the mean of the S_b+n value rows, seq_lens[b]
- * += n.  If S_b + n > S_max the sequence is left untouched and SPARQ_ERR_APPEND_FULL is
+ * For sequence b with n rows: rows land at positions S_b..S_b+n-1 of K and V; Kt is brought up to date
+ * to column 8 * floor((S_b+n) / 8) at least (NOT to S_b+n: Kt trails K by up to 7 columns, see the cache
+ * layout above; the decode calls take those keys from K); v_mean becomes the mean of the S_b+n value
+ * rows (for S_b = 0 the old content of v_mean is ignored); seq_lens[b] += n.  If S_b + n > S_max the sequence is left untouched and SPARQ_ERR_APPEND_FULL is
  * raised in the error word.  The only call that mutates the cache.
  */
 int sparq_kv_append(const sparq_shape* shape, const sparq_cache* cache, const void* k_new,
@@ -128,7 +139,7 @@ int sparq_kv_append(const sparq_shape* shape, const sparq_cache* cache, const vo
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
- * One SparQ decode step for all B x H heads (Section 4, Steps 1-3; Section 3 Eqs. 5-8).
+ * One SparQ decode step for all B x H heads (Section 4, Steps 1-3; Section 3 Eqs. 7-10).
  * Per query head, over the rows 0..S_b-1 of its KV head:
  *   Step 1  i1 = the r largest |q_j| (ties to the lower j);
  *           tau = sqrt(d_h * sum_{j in i1}|q_j| / sum_j |q_j|)  (sqrt(d_h) if q = 0);
@@ -176,7 +187,7 @@ int sparq_decode_step(const sparq_shape* shape, const sparq_cache* cache, const 
 
 /*
  * Dense single-query attention y = softmax(q K^T / sqrt(d_h)) V over rows 0..S_b-1
- * (Section 3, Eq. 1): the in-library comparison.  Reads K and V once per KV head for
+ * (Section 3, Eq. 2): the in-library comparison.  Reads K and V once per KV head for
  * all g query heads of the group.  Uses the workspace for split-sequence partials.
  *   q, out  device [B, H, d_h], cache dtype
  */
@@ -194,6 +205,10 @@ int sparq_copy_probe(void* dst, const void* src, size_t n_bytes, void* hip_strea
 /* Plain streaming read of n_bytes (multiple of 16) by the same grid; each thread stores one
  * folded word to `sink` (device, at least 2 MiB = 2048 workgroups x 256 threads x 4 bytes). */
 int sparq_read_probe(const void* src, size_t n_bytes, void* sink, size_t sink_bytes, void* hip_stream);
+
+/* Which kernels sparq_decode / sparq_decode_step launch for this shape (a static string naming the plan
+ * and its launches; "unsupported" where sparq_decode would return SPARQ_EUNSUPPORTED).  Host only. */
+const char* sparq_decode_plan(const sparq_shape* shape);
 
 const char* sparq_status_string(int status);
 

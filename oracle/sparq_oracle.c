@@ -8,9 +8,13 @@
  * the paper's order, fp64 arithmetic on the exactly-converted 16-bit inputs,
  * full sorts instead of selection, no blocking, no fusion.
  *
+ * Equation numbers are the paper's own, counted from its first displayed equation: (2) dense
+ * attention, (3) M_dense, (6) mean value reallocation, (7) approximate scores, (8) attention over
+ * the selected positions, (9) temperature, (10) blend with the mean value vector.
+ *
  * What each function follows:
- *   oracle_dense_decode      Section 3, Eq. (1)  (dense single-query attention)
- *   oracle_sparq_decode      Section 3 Eqs. (5)-(8), Section 4 Steps 1-3,
+ *   oracle_dense_decode      Section 3, Eq. (2)  (dense single-query attention)
+ *   oracle_sparq_decode      Section 3 Eqs. (7)-(10), Section 4 Steps 1-3,
  *                            the GQA paragraph of Section 4, Appendix B
  *   oracle_mean_value        Section 3, "Mean value reallocation" (definition of v-bar)
  *   oracle_to_double         exact widening of IEEE binary16 / bfloat16
@@ -24,8 +28,8 @@
  *   - in grouped-query "shared" mode the group sum of s-hat decides the positions,
  *     tau and alpha stay per query head (Appendix B).
  *
- * Pins (tests/test_oracle_pins.py): r = d_h and k = S reproduces Eq. (1);
- * r = d_h with any k reproduces Eq. (4); the schematic's worked query; the
+ * Pins (tests/test_oracle_pins.py): r = d_h and k = S reproduces Eq. (2);
+ * r = d_h with any k reproduces Eq. (6); the schematic's worked query; the
  * sqrt(r) <= tau <= sqrt(d_h) range; alpha = k/S for identical keys; brute
  * force on tiny inputs; permutation invariances; conversion of all 65536 codes.
  */
@@ -116,7 +120,7 @@ int oracle_mean_value(int B, int H_kv, int S_max, int d_h, int dtype, const uint
   return 0;
 }
 
-/* ---- Eq. (1): y = softmax(q K^T / sqrt(d_h)) V over the rows in `rows` ----------- */
+/* ---- Eq. (2): y = softmax(q K^T / sqrt(d_h)) V over the rows in `rows` ----------- */
 
 /* exact attention restricted to the listed rows (all rows for the dense case) */
 static void attention_over_rows(const double* q, const uint16_t* K, const uint16_t* V, int d_h,
@@ -147,7 +151,7 @@ int oracle_dense_decode(int B, int H, int H_kv, int S_max, int d_h, int dtype,
   if (B < 1 || H < 1 || H_kv < 1 || H % H_kv || d_h < 1 || S_max < 1) return -1;
   int g = H / H_kv;
   int fail = 0;
-#pragma omp parallel for collapse(2) schedule(dynamic)
+#pragma omp parallel for collapse(2) schedule(dynamic) reduction(|:fail)
   for (int b = 0; b < B; ++b)
     for (int h = 0; h < H; ++h) {
       int S = seq_lens[b];
@@ -208,7 +212,7 @@ static void sparq_group(const group_job* J) {
     }
   }
 
-  /* Step 1 continued: temperature (Eq. 7) and approximate scores (Eq. 5), per query head */
+  /* Step 1 continued: temperature (Eq. 9) and approximate scores (Eq. 7), per query head */
   for (int t = 0; t < g; ++t) {
     const double* qt = qd + t * d_h;
     const int* i1 = chan + t * r;
@@ -276,10 +280,10 @@ static void sparq_group(const group_job* J) {
     for (int n = 0; n < J->k_stride; ++n)
       J->i2[(size_t)t * J->k_stride + n] = n < n_pos ? pos[n] : -1;
 
-    /* Step 2: exact attention over the selected rows (Eq. 6 with epsilon -> 0) */
+    /* Step 2: exact attention over the selected rows (Eq. 8 with epsilon -> 0) */
     attention_over_rows(qd + t * d_h, J->K, J->V, d_h, dtype, pos, n_pos, y3);
 
-    /* Step 3: alpha = mass of the selected positions under s-hat; blend with v-bar (Eq. 8) */
+    /* Step 3: alpha = mass of the selected positions under s-hat; blend with v-bar (Eq. 10) */
     double alpha = 0.0;
     for (int n = 0; n < n_pos; ++n) alpha += shat[(size_t)t * S + pos[n]];
     J->alpha[t] = alpha;

@@ -26,7 +26,8 @@ _lib = None
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        path = _build.build()
+        # SPARQ_ORACLE_SANITIZED=1: the AddressSanitizer + UBSan build (the process must preload libasan)
+        path = _build.build(sanitize=bool(os.environ.get("SPARQ_ORACLE_SANITIZED")))
         L = ctypes.CDLL(path)
         c_int, c_uint, c_long, vp = ctypes.c_int, ctypes.c_uint, ctypes.c_long, ctypes.c_void_p
         L.oracle_to_double.argtypes = [c_int, vp, c_long, vp]
@@ -104,7 +105,7 @@ def sparq_decode(K, V, q, seq_lens, *, r, k, dtype, flags=0, k_per_seq=None, giv
 
 
 def dense_decode(K, V, q, seq_lens, *, dtype) -> np.ndarray:
-    """Dense single-query attention, Eq. (1)."""
+    """Dense single-query attention, Eq. (2)."""
     B, H_kv, S_max, d_h = K.shape
     H = q.shape[1]
     K = _u16(K, (B, H_kv, S_max, d_h)); V = _u16(V, (B, H_kv, S_max, d_h)); q = _u16(q, (B, H, d_h))

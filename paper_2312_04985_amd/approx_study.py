@@ -50,7 +50,7 @@ def run(S: int, q_scale: float, seed: int):
     print()
     print("| r = 32, k = 256, variant | top-k correspondence | rel. error | mean alpha |")
     print("|---|---|---|---|")
-    for name, flags, window in (("Eq. (7) temperature", 0, 0), ("tau = sqrt(d_h)", B.SPARQ_FLAG_TAU_SQRT_DH, 0),
+    for name, flags, window in (("Eq. (9) temperature", 0, 0), ("tau = sqrt(d_h)", B.SPARQ_FLAG_TAU_SQRT_DH, 0),
                                 ("tau = sqrt(r)", B.SPARQ_FLAG_TAU_SQRT_R, 0), ("no mean-value blend", B.SPARQ_FLAG_NO_REALLOC, 0),
                                 ("local window 64", 0, 64)):
         corr, err, al = measure(32, 256, flags, window)

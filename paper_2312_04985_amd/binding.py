@@ -22,7 +22,8 @@ SPARQ_ERR_APPEND_FULL, SPARQ_ERR_EMPTY_SEQ, SPARQ_ERR_IDX_TRUNCATED, SPARQ_ERR_B
 SPARQ_OK, SPARQ_EINVAL, SPARQ_EUNSUPPORTED, SPARQ_EWORKSPACE, SPARQ_ELAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ["sparq_workspace_bytes", "sparq_workspace_init", "sparq_kv_append", "sparq_decode", "sparq_decode_step",
-           "dense_decode", "sparq_async_error", "sparq_copy_probe", "sparq_read_probe", "sparq_status_string"]
+           "dense_decode", "sparq_async_error", "sparq_copy_probe", "sparq_read_probe", "sparq_decode_plan",
+           "sparq_status_string"]
 
 
 class SparqShape(ctypes.Structure):
@@ -67,12 +68,18 @@ def load() -> ctypes.CDLL:
     L.sparq_copy_probe.argtypes = [vp, vp, sz, vp]
     L.sparq_read_probe.argtypes = [vp, sz, vp, sz, vp]
     L.sparq_status_string.argtypes = [ctypes.c_int]
+    L.sparq_decode_plan.argtypes = [shp]
+    L.sparq_decode_plan.restype = ctypes.c_char_p
     L.sparq_status_string.restype = ctypes.c_char_p
     for name in EXPORTS:
-        if name != "sparq_status_string":
+        if name not in ("sparq_status_string", "sparq_decode_plan"):
             getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
+
+
+def sparq_decode_plan(shape: SparqShape) -> str:
+    return load().sparq_decode_plan(ctypes.byref(shape)).decode()
 
 
 def status_string(status: int) -> str:

@@ -433,6 +433,19 @@ int sparq_read_probe(const void* src, size_t n_bytes, void* sink, size_t sink_by
   return launch_read_probe(src, n_bytes, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
+const char* sparq_decode_plan(const sparq_shape* shape) {
+  if (check_shape(shape) != SPARQ_OK) return "invalid shape";
+  switch (choose_plan(shape).plan) {
+    case kPlanFused: return "sparq_decode_fused (one workgroup per head, one launch)";
+    case kPlanSplit: return "split_scores + split_select + split_gather + split_combine (split-sequence plan)";
+    case kPlanLong: return "long_scores + long_merge + split_gather + split_combine (two-level selection plan)";
+    case kPlanShared: return "sparq_decode_shared (grouped-query rule, one workgroup per KV head)";
+    case kPlanSharedSplit: return "gs_logits + gs_select + gs_merge + gs_gather + split_combine (grouped-query rule, several workgroups per KV head)";
+    case kPlanSingleK: return "sparq_decode_single_k (key cache stored once)";
+    default: return "unsupported";
+  }
+}
+
 const char* sparq_status_string(int status) {
   switch (status) {
     case SPARQ_OK: return "ok";

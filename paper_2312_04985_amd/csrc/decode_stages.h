@@ -78,7 +78,7 @@ __device__ __forceinline__ void find_threshold_bin(const uint32_t* hist, int nee
 }
 
 // ------------------------------------------------------------------------------------------------
-// Step 1a: the r largest components of |q| (ties to the lower channel) and the temperature (Eq. 7)
+// Step 1a: the r largest components of |q| (ties to the lower channel) and the temperature (Eq. 9)
 
 struct QueryLds {
   uint32_t* mag;   // [DH] sort keys
@@ -147,7 +147,7 @@ __device__ __forceinline__ float select_channels(const QueryLds& Q, uint16_t qco
   return tau;
 }
 
-// The temperature actually used: Eq. (7), or one of the two fixed values of the ablation in Section 5.3
+// The temperature actually used: Eq. (9), or one of the two fixed values of the ablation in Section 5.3
 // (flag bits 3 and 4).
 __device__ __forceinline__ float apply_tau_mode(float tau_l1, uint32_t flags, int d_h, int r) {
   if (flags & 8u) return sqrtf((float)d_h);
@@ -444,7 +444,7 @@ __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t
 }
 
 // ------------------------------------------------------------------------------------------------
-// Step 2b: exact softmax attention over gathered rows (Eq. 6), online softmax in the exp2 domain
+// Step 2b: exact softmax attention over gathered rows (Eq. 8), online softmax in the exp2 domain
 
 template <int DH>
 struct RowGeometry {

@@ -1,4 +1,4 @@
-// Dense single-query attention (Section 3, Eq. 1): the in-library comparison for SparQ.
+// Dense single-query attention (Section 3, Eq. 2): the in-library comparison for SparQ.
 // Split along the sequence: each workgroup streams a run of K and V rows of one KV head once
 // for G query heads of its group (online softmax, fp32), writes (acc, m, l) partials; a second
 // kernel merges the partials of each query head.

@@ -34,7 +34,7 @@ struct GroupQueryLds {
 };
 
 // Step 1a under the group rule: channel j is ranked by sum_h |q_h,j| (fp64, heads in order, ties to the lower
-// channel); esc[h] = log2(e) / tau_h with tau_h from Eq. (7) on the shared channel set (or the fixed
+// channel); esc[h] = log2(e) / tau_h with tau_h from Eq. (9) on the shared channel set (or the fixed
 // temperature the flags ask for).  q_group: the G x DH query codes of the group.  Four barriers; the first also
 // publishes whatever the caller wrote to LDS before the call.
 template <class T, int DH, int G>

@@ -55,6 +55,7 @@ __global__ __launch_bounds__(512) void append_one_row(const AppendArgs a) {
     const float* vm = a.v_mean + head * a.d_h + j0;
     float* vo = a.v_mean_out + head * a.d_h + j0;
     float4 m0 = *reinterpret_cast<const float4*>(vm), m1 = *reinterpret_cast<const float4*>(vm + 4);
+    if (S == 0) m0 = m1 = make_float4(0.f, 0.f, 0.f, 0.f);   // the mean of no rows: whatever the buffer held is ignored
     float f[8];
     unpack8<T>(vc, f);
     m0.x += (f[0] - m0.x) * inv; m0.y += (f[1] - m0.y) * inv; m0.z += (f[2] - m0.z) * inv; m0.w += (f[3] - m0.w) * inv;
@@ -134,7 +135,8 @@ __global__ __launch_bounds__(BT) void append_rows(const AppendArgs a) {
     double tot = 0.0;
     for (int p = 0; p < RPP; ++p) tot += colsum[p][tid];
     float* vm = a.v_mean + head * DH + tid;
-    *vm = (float)(((double)S * (double)*vm + tot) / (double)(S + n));
+    const double before = S > 0 ? (double)S * (double)*vm : 0.0;   // S = 0: whatever the buffer held is ignored
+    *vm = (float)((before + tot) / (double)(S + n));
   }
 }
 

@@ -1,13 +1,13 @@
 // SparQ decode, one workgroup per (sequence, query head): Section 4, Steps 1-3, in one launch with
 // no intermediate HBM traffic.
-//   stage 0  top-r of |q| and the temperature (Eq. 7)
+//   stage 0  top-r of |q| and the temperature (Eq. 9)
 //   stage 1  stream the r selected rows of the S-contiguous key copy; the fp32 approximate logit
 //            numerators of all cached positions stay in LDS as order-preserving integer keys and are
 //            counted into the first radix histogram as they are produced
 //   stage 2  radix select of the k-th largest key, ordered compaction of the selected positions
 //            (ties to the lower position), alpha = selected share of the approximate softmax mass
 //   stage 3  gather the selected K and V rows, online-softmax exact attention, blend with the
-//            mean value vector (Eq. 8), round and store
+//            mean value vector (Eq. 10), round and store
 #include "decode_stages.h"
 
 namespace sparq {
@@ -45,8 +45,8 @@ __device__ __forceinline__ Lds carve(uint32_t* base, int S_max) {
 // APPEND = true is the one-launch decode step: the new key/value row of every KV head (k_new, v_new)
 // counts as position S_b of its sequence without being read back from the cache.  Every workgroup
 // takes that row from the inputs; the workgroup of the first query head of a KV group also writes
-// it into K, V and Kt and stores the updated mean; lengths and means go to the *_next buffers, so
-// no workgroup can observe another one's update of the state it reads.
+// it into K, V and Kt and stores the updated mean; lengths and means go to the *_next buffers, so no
+// workgroup can observe another one's update of the state it reads.
 template <class T, int DH, bool APPEND>
 __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) {
   extern __shared__ __align__(16) uint32_t smem[];
@@ -78,9 +78,13 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   const int hk = h / (a.H / a.H_kv);
   const size_t kv_head = (size_t)b * a.H_kv + hk;
 
+  // everything the unit reads from small tensors is requested here, in one round trip; the mean value
+  // vector is only needed for the blend at the very end
   uint16_t qcode = 0, kcode = 0, vcode = 0;
+  float vm = 0.0f;
   if (tid < DH) {
     qcode = reinterpret_cast<const uint16_t*>(a.q)[(size_t)u * DH + tid];
+    vm = a.v_mean[kv_head * DH + tid];
     if (APPEND) {
       kcode = reinterpret_cast<const uint16_t*>(a.k_new)[kv_head * DH + tid];
       vcode = reinterpret_cast<const uint16_t*>(a.v_new)[kv_head * DH + tid];
@@ -109,8 +113,12 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
     if (tid == 0) { atomicOr(a.err, 2); if (a.alpha_out) a.alpha_out[u] = 0.0f; }
     if (a.chan_out && tid < a.r) a.chan_out[(size_t)u * a.r + tid] = -1;
     if (idx_out) for (int n = tid; n < a.idx_stride; n += NT) idx_out[n] = -1;
-    if (owner && tid < DH) a.v_mean_next[kv_head * DH + tid] = a.v_mean[kv_head * DH + tid];
+    if (owner && tid < DH) a.v_mean_next[kv_head * DH + tid] = vm;
     return;
+  }
+  if (APPEND && appended && tid < DH) {   // same update as append_one_row; the mean of no rows is ignored
+    if (S == 1) vm = 0.0f;
+    vm += (T::widen(vcode) - vm) * (1.0f / (float)S);
   }
 
   // ---------------- stage 0 ----------------
@@ -118,11 +126,12 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   if (APPEND && tid < DH) { L.knew[tid] = kcode; L.vnew[tid] = vcode; }
   const float tau = apply_tau_mode(select_channels<T, DH>(L.qry, qcode, a.r, tid, lane, wave), a.flags, DH, a.r);
   const Window win = make_window(a.local_window, S, kq);
+  if (tid < DH) L.qry.mag[tid] = __float_as_uint(vm);   // parked in LDS until the blend (the ranking keys are dead)
   if (a.chan_out && tid < a.r) a.chan_out[(size_t)u * a.r + tid] = L.qry.chan[tid];
   // the newest S mod 8 positions are not in Kt: wave w gets position S_fl + w from its K row (from the
   // inputs if it is the row being appended); loads issued here, used after stage 1
   // (in the one-launch step Kt is up to date for the length before this call: the group of 8 that the new
-  // row may complete is written at the end of this launch, so up to 8 positions come from rows)
+  // row may complete is written during this launch, so up to 8 positions come from rows)
   const int S_fl = ((APPEND && appended) ? S - 1 : S) & ~7, n_tail = S - S_fl, r8 = (a.r + 7) & ~7;
   const uint16_t* K_rows = reinterpret_cast<const uint16_t*>(a.K) + kv_head * a.S_max * (size_t)DH;
   TailRow tail;
@@ -136,8 +145,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   const size_t row_bytes = (size_t)a.S_max * 2;
   const char* Kt_head = reinterpret_cast<const char*>(a.Kt) + kv_head * DH * row_bytes;
   float tmax = -INFINITY;
-  stream_channel_rows<T>(Kt_head, row_bytes, L.qry.chan, L.qry.qs, a.r, 0, S_fl >> 3, tid,
-                         [&](int c, const float (&acc)[8]) {
+  auto finish = [&](int c, const float (&acc)[8]) {
     uint32_t kx[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -148,7 +156,8 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
     uint4* dst = reinterpret_cast<uint4*>(L.keys + c * 8);
     dst[0] = make_uint4(kx[0], kx[1], kx[2], kx[3]);
     dst[1] = make_uint4(kx[4], kx[5], kx[6], kx[7]);
-  });
+  };
+  stream_channel_rows<T>(Kt_head, row_bytes, L.qry.chan, L.qry.qs, a.r, 0, S_fl >> 3, tid, finish);
   if (wave < n_tail) {
     const float dot = tail_row_dot<T>(tail, L.qry.qs, r8, lane);
     tmax = fmaxf(tmax, dot);
@@ -200,26 +209,26 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
     float m_all, l_all, y3;
     combine_partials<DH>(L.part, NW, tid, m_all, l_all, y3);
     y3 /= l_all;
-    float vm = a.v_mean[kv_head * DH + tid];
-    if (APPEND) {
-      if (appended) vm += (T::widen(L.vnew[tid]) - vm) * (1.0f / (float)S);   // same update as append_one_row
-      if (owner) a.v_mean_next[kv_head * DH + tid] = vm;
-    }
     float y = y3;
-    if (!(a.flags & 1u)) y = alpha * y3 + (1.0f - alpha) * vm;
+    if (!(a.flags & 1u)) y = alpha * y3 + (1.0f - alpha) * __uint_as_float(L.qry.mag[tid]);
     out[tid] = T::narrow(y);
   }
-  if (APPEND && owner && appended) {
-    // the row into both key layouts and the value cache
-    uint16_t* Krow = reinterpret_cast<uint16_t*>(a.K) + (kv_head * a.S_max + (S - 1)) * DH;
-    uint16_t* Vrow = reinterpret_cast<uint16_t*>(a.V) + (kv_head * a.S_max + (S - 1)) * DH;
-    if (tid < DH / 8) {
-      reinterpret_cast<uint4*>(Krow)[tid] = reinterpret_cast<const uint4*>(L.knew)[tid];
-      reinterpret_cast<uint4*>(Vrow)[tid] = reinterpret_cast<const uint4*>(L.vnew)[tid];
+  if (APPEND && owner && tid < DH) {
+    // The append's stores come last.  (Measured at five places of the kernel: in front of stage 0 they sit
+    // on the critical path of every wait that follows, because a wait for a load also waits for the stores
+    // issued before it; after Step 1b, after the select, after the compaction and here cost the same within
+    // noise when workgroups come in several rounds, and here is best when they all run at once.)  Nobody
+    // reads row S - 1 of K or V in this launch (every head takes it from k_new / v_new), the new mean goes to
+    // the *_next buffer, and the columns written to Kt lie above S_fl for every head of the group.
+    a.v_mean_next[kv_head * DH + tid] = __uint_as_float(L.qry.mag[tid]);
+    if (appended) {
+      const uint16_t kc = L.knew[tid];
+      reinterpret_cast<uint16_t*>(a.K)[(kv_head * a.S_max + (S - 1)) * DH + tid] = kc;
+      reinterpret_cast<uint16_t*>(a.V)[(kv_head * a.S_max + (S - 1)) * DH + tid] = L.vnew[tid];
+      // a step that completes a group of 8 positions copies it to Kt (one 16-byte store per channel row)
+      if ((S & 7) == 0)
+        flush_key_columns(reinterpret_cast<uint16_t*>(a.Kt) + kv_head * DH * (size_t)a.S_max, K_rows, a.S_max, DH, S, tid, kc);
     }
-    // the S-contiguous copy advances 8 positions at a time
-    if ((S & 7) == 0 && tid < DH)
-      flush_key_columns(reinterpret_cast<uint16_t*>(a.Kt) + kv_head * DH * (size_t)a.S_max, K_rows, a.S_max, DH, S, tid, L.knew[tid]);
   }
 }
 
@@ -227,11 +236,8 @@ template <class T, int DH, bool APPEND>
 hipError_t launch_one(const DecodeArgs& a, hipStream_t s) {
   const size_t lds = decode_lds_bytes(a.S_max, DH);
   auto kern = sparq_decode_fused<T, DH, APPEND>;
-  if (lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-  }
+  hipError_t e = allow_lds<sparq_decode_fused<T, DH, APPEND>>(lds);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(a.B * a.H), dim3(NT), lds, s, a);
   return hipGetLastError();
 }

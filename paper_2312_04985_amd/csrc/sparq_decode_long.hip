@@ -250,12 +250,8 @@ hipError_t launch_long(const LongArgs& a, int dtype, hipStream_t s) {
   const size_t lds1 = 4 * ((size_t)a.span_len + scores_fixed_words<DH>()), lds2 = long_merge_lds_bytes(a.n_span, a.cand_cap);
   auto k1 = long_scores<T, DH>;
   hipError_t e;
-  if (lds1 > 64 * 1024 &&
-      (e = hipFuncSetAttribute(reinterpret_cast<const void*>(k1), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1)) != hipSuccess)
-    return e;
-  if (lds2 > 64 * 1024 &&
-      (e = hipFuncSetAttribute(reinterpret_cast<const void*>(long_merge), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2)) != hipSuccess)
-    return e;
+  if ((e = allow_lds<long_scores<T, DH>>(lds1)) != hipSuccess) return e;
+  if ((e = allow_lds<long_merge>(lds2)) != hipSuccess) return e;
   hipLaunchKernelGGL(k1, dim3(units * a.n_span), dim3(NT), lds1, s, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(long_merge, dim3(units), dim3(NT), lds2, s, a);

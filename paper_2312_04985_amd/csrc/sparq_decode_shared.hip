@@ -9,7 +9,7 @@
 //   stage 2  radix select of the k largest scores, ordered position list
 //   stage 3  gather each selected K and V row once for the G heads: exact attention per head; per-head
 //            alpha from the stored logits of the selected positions
-//   blend    y_h = alpha_h y3_h + (1 - alpha_h) v_mean (Eq. 8), round and store
+//   blend    y_h = alpha_h y3_h + (1 - alpha_h) v_mean (Eq. 10), round and store
 // The group sum of softmaxes is not monotone in any one head's logits, so the logits themselves are needed
 // twice (statistics, then scores) and a third time for alpha; G x S floats do not fit in LDS for long
 // sequences, so they live in the workspace (16 bytes per position for G = 4, against 2 r bytes for streaming
@@ -337,11 +337,8 @@ template <class T, int DH, int G>
 hipError_t launch_shared_g(const DecodeArgs& a, float* z_ws, hipStream_t s) {
   const size_t lds = 4 * ((size_t)a.S_max + shared_fixed_words<DH, G>());
   auto kern = sparq_decode_shared<T, DH, G>;
-  if (lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-  }
+  hipError_t e = allow_lds<sparq_decode_shared<T, DH, G>>(lds);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(a.B * a.H_kv), dim3(NT), lds, s, a, z_ws);
   return hipGetLastError();
 }

@@ -9,7 +9,7 @@
 //   gs_merge    (one workgroup per KV unit) select over the candidates, position list, alpha per head from
 //               the stored logits of the selected positions
 //   gs_gather   (KV units x n_split) each selected K and V row once for the G heads, partials per head
-//   split_combine  (one workgroup per query head) merge, blend with the mean value vector (Eq. 8), store
+//   split_combine  (one workgroup per query head) merge, blend with the mean value vector (Eq. 10), store
 #include "group_stages.h"
 
 namespace sparq {
@@ -482,12 +482,8 @@ hipError_t launch_gs(const GsArgs& a, int dtype, hipStream_t s) {
   const int Ukv = a.d.B * a.d.H_kv;
   const size_t lds2 = gs_select_lds_bytes(a.span2), lds3 = gs_merge_lds_bytes(a.n2, a.cand_cap);
   hipError_t e;
-  if (lds2 > 64 * 1024 &&
-      (e = hipFuncSetAttribute(reinterpret_cast<const void*>(gs_select<G>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2)) != hipSuccess)
-    return e;
-  if (lds3 > 64 * 1024 &&
-      (e = hipFuncSetAttribute(reinterpret_cast<const void*>(gs_merge<G>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds3)) != hipSuccess)
-    return e;
+  if ((e = allow_lds<gs_select<G>>(lds2)) != hipSuccess) return e;
+  if ((e = allow_lds<gs_merge<G>>(lds3)) != hipSuccess) return e;
   hipLaunchKernelGGL((gs_logits<T, DH, G>), dim3(Ukv * a.n1), dim3(NT), 0, s, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(gs_select<G>, dim3(Ukv * a.n2), dim3(NT), lds2, s, a);

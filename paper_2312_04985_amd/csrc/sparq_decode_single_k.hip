@@ -196,11 +196,8 @@ template <class T, int DH>
 hipError_t launch_1k(const DecodeArgs& a, hipStream_t s) {
   const size_t lds = 4 * ((size_t)a.S_max + lds_words_1k<DH>());
   auto kern = sparq_decode_single_k<T, DH>;
-  if (lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-  }
+  hipError_t e = allow_lds<sparq_decode_single_k<T, DH>>(lds);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(a.B * a.H), dim3(NT), lds, s, a);
   return hipGetLastError();
 }

@@ -7,7 +7,7 @@
 //                  alpha to the workspace
 //   split_gather   (units x n_split) exact attention over a slice of the position list -> partial
 //                  (numerator, max, denominator)
-//   split_combine  (one workgroup per unit) merge, blend with the mean value vector (Eq. 8), store
+//   split_combine  (one workgroup per unit) merge, blend with the mean value vector (Eq. 10), store
 #include "decode_stages.h"
 
 namespace sparq {
@@ -261,13 +261,10 @@ hipError_t launch_pair(const SplitArgs& a, hipStream_t s) {
   const int units = a.d.B * a.d.H;
   const dim3 grid(units * a.n_split);
   const size_t lds = split_select_lds_bytes(a.d.S_max);
-  if (lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(split_select),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-  }
+  hipError_t e = allow_lds<split_select>(lds);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL((split_scores<T, DH>), grid, dim3(NT), 0, s, a);
-  hipError_t e = hipGetLastError();
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(split_select, dim3(units), dim3(NT), lds, s, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;

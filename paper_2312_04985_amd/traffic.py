@@ -1,6 +1,6 @@
 """Transfer model of the decode step: what the method must move, per head and per step.
 
-Element counts follow the paper's two transfer equations (Section 3, Eq. 2 for dense
+Element counts follow the paper's two transfer equations (Section 3, Eq. 3 for dense
 attention; Section 4 for SparQ); the byte figures used for the roofline split the SparQ
 count into its stages.  Nothing here touches a GPU.
 """
@@ -10,7 +10,7 @@ from typing import Iterable, Optional
 
 
 def dense_elements(S: int, d_h: int) -> int:
-    """M_dense = 2 S d_h + 2 d_h : read K and V, write the new k and v (Section 3, Eq. 2)."""
+    """M_dense = 2 S d_h + 2 d_h : read K and V, write the new k and v (Section 3, Eq. 3)."""
     return 2 * S * d_h + 2 * d_h
 
 

@@ -1,17 +1,18 @@
 """GPU parity at the full sizes of the five named workloads, in the launch configuration the
-benchmark uses.  The whole batch runs on the GPU; the oracle checks a seeded sample of
-(sequence, KV head) units (all query heads of each), whose rows alone are copied to the host."""
-import sys
-
+benchmark uses.  The whole batch runs on the GPU.  For configs 1-4 the oracle runs on the whole batch too and
+every (sequence, head) unit is compared (cache state, channel sets, position sets, alpha, output, dense
+output); for the ragged config 5 and the paper's microbenchmark shape the oracle checks a seeded sample of
+(sequence, KV head) units, whose rows alone are copied to the host."""
 import pytest
 import torch
 
 from paper_2312_04985_amd import binding as B
 from paper_2312_04985_amd import workloads as W
+from paper_2312_04985_amd.cache import DecodeCache
 
 import harness as Hn
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 C = W.CONFIGS
 
 
@@ -19,31 +20,48 @@ def say(*a):
     print(*a, flush=True)
 
 
-@pytest.mark.parametrize("name,n_units,singles", [
-    ("c1_single_head", 1, 2), ("c2_llama2_7b", 48, 2), ("c3_llama3_8b_gqa", 8, 1),
-    ("c4_large_batch", 40, 1), ("c5_gemma_7b_ragged", 24, 1), ("paper_table2", 32, 1)])
-def test_full_size_sampled(name, n_units, singles):
+@pytest.mark.parametrize("name,q_scale", [
+    ("c1_single_head", 1.0), ("c2_llama2_7b", 1.0), ("c3_llama3_8b_gqa", 1.0), ("c4_large_batch", 1.0),
+    # the planted queries make attention nearly one-hot (alpha ~ 1, where a wrong (1 - alpha) v_mean term could
+    # hide); scaled-down queries with offset values put alpha mid-range at full size
+    ("c2_llama2_7b", 0.02), ("c4_large_batch", 0.02)])
+def test_full_size_every_unit(name, q_scale):
     w = C[name]
-    say(f"[full-size] {name}: B={w.B} H={w.H}/{w.H_kv} d_h={w.d_h} S={w.S} r={w.r} k={w.k} {w.dtype} ragged={w.ragged}")
-    b = Hn.build_cache(w, single_appends=singles, poison=None)
+    say(f"[full-size] {name}: B={w.B} H={w.H}/{w.H_kv} d_h={w.d_h} S={w.S} r={w.r} k={w.k} {w.dtype} q_scale={q_scale}")
+    b = Hn.build_cache(w, single_appends=2 if w.B * w.H_kv <= 512 else 1, poison=None, v_offset=q_scale != 1.0)
     say("   cache built:", tuple(b.cache.K.shape), "seq_lens", b.seq_lens[:8].tolist())
-    q = W.draw_queries(w, b.K_src, b.seq_lens, n=1)[0]
-    flags = B.SPARQ_FLAG_RAGGED_BATCH if w.ragged else 0           # as bench.py launches it
-    stats = Hn.compare_sampled(b, q, n_units=n_units, seed=w.seed, flags=flags)
+    q = W.draw_queries(w, b.K_src, b.seq_lens, n=1, q_scale=q_scale)[0]
+    stats = Hn.compare_decode(b, q)
     say("   ", stats)
+    assert stats["units"] == w.B * w.H
+    if q_scale != 1.0:
+        assert stats["alpha_min"] < 0.9, "this case is there for mid-range alpha"
     del b
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("name,n_units", [("c2_llama2_7b", 48), ("c4_large_batch", 24), ("c5_gemma_7b_ragged", 16)])
-def test_full_size_one_launch_step(name, n_units):
-    """The launch the benchmark times: sparq_decode_step on the full batch, the new row landing at S_b - 1
-    of every sequence; sampled units against the oracle on the grown cache, cache state included."""
+@pytest.mark.parametrize("name,n_units,q_scale", [("c5_gemma_7b_ragged", 24, 1.0), ("c5_gemma_7b_ragged", 16, 0.02),
+                                                  ("paper_table2", 32, 1.0)])
+def test_full_size_sampled(name, n_units, q_scale):
+    w = C[name]
+    say(f"[full-size, sampled] {name}: B={w.B} H={w.H}/{w.H_kv} d_h={w.d_h} S={w.S} r={w.r} k={w.k} {w.dtype} ragged={w.ragged}")
+    b = Hn.build_cache(w, single_appends=1, poison=None, v_offset=q_scale != 1.0)
+    q = W.draw_queries(w, b.K_src, b.seq_lens, n=1, q_scale=q_scale)[0]
+    flags = B.SPARQ_FLAG_RAGGED_BATCH if w.ragged else 0           # as bench.py launches it
+    stats = Hn.compare_sampled(b, q, n_units=n_units, seed=w.seed, flags=flags)
+    say("   ", stats)
+    if q_scale != 1.0:
+        assert stats["alpha_min"] < 0.9, "this case is there for mid-range alpha"
+    del b
+    torch.cuda.empty_cache()
+
+
+def step_case(name):
+    """Cache filled up to the last row but one, and the rows the step appends."""
     w = C[name]
     seq = W.draw_seq_lens(w)                       # lengths AFTER the step
     K_src, V_src = W.draw_kv(w, "cuda", n_rows=int(seq.max()))
     S_max = W.round_up(int(seq.max()), 64)
-    from paper_2312_04985_amd.cache import DecodeCache
     flags = B.SPARQ_FLAG_RAGGED_BATCH if w.ragged else 0
     c = DecodeCache(w.B, w.H, w.H_kv, S_max, w.d_h, w.r, w.k, w.torch_dtype, flags=flags)
     c.append(K_src, V_src, (seq - 1).cuda())       # all but the last row of every sequence
@@ -51,9 +69,26 @@ def test_full_size_one_launch_step(name, n_units):
     k_new = K_src.gather(2, last).squeeze(2).contiguous(); v_new = V_src.gather(2, last).squeeze(2).contiguous()
     b = Hn.Built(w, c, K_src, V_src, seq, W.k_per_seq(w, seq))
     q = W.draw_queries(w, K_src, seq, n=1)[0]
-    say(f"[full-size step] {name}: seq_lens {seq[:6].tolist()}")
-    stats = Hn.compare_sampled(b, q, n_units=n_units, seed=w.seed + 1, flags=flags, with_dense=False,
-                               step_rows=(k_new, v_new))
+    return w, b, q, k_new, v_new, flags
+
+
+@pytest.mark.parametrize("name", ["c2_llama2_7b", "c4_large_batch"])
+def test_full_size_one_launch_step_every_unit(name):
+    """The launch the benchmark times: sparq_decode_step on the full batch, the new row landing at S_b - 1
+    of every sequence; every unit against the oracle on the grown cache, cache state included."""
+    w, b, q, k_new, v_new, flags = step_case(name)
+    say(f"[full-size step] {name}: seq_lens {b.seq_lens[:6].tolist()}")
+    stats = Hn.compare_decode(b, q, flags=flags, step_rows=(k_new, v_new))
     say("   ", stats)
-    del b, c
+    assert stats["units"] == w.B * w.H
+    del b
+    torch.cuda.empty_cache()
+
+
+def test_full_size_one_launch_step_ragged_sampled():
+    w, b, q, k_new, v_new, flags = step_case("c5_gemma_7b_ragged")
+    say(f"[full-size step, sampled] {w.name}: seq_lens {b.seq_lens[:6].tolist()}")
+    stats = Hn.compare_sampled(b, q, n_units=16, seed=w.seed + 1, flags=flags, with_dense=False, step_rows=(k_new, v_new))
+    say("   ", stats)
+    del b
     torch.cuda.empty_cache()

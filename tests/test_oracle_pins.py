@@ -29,7 +29,7 @@ def rand_case(seed, B=1, H=1, H_kv=1, S=48, d_h=16, dtype=F16, S_max=None, scale
 
 
 def np_dense(q, K, V):
-    """Eq. (1) with library routines: q [d], K, V [S, d]."""
+    """Eq. (2) with library routines: q [d], K, V [S, d]."""
     return scipy_softmax(K @ q / math.sqrt(len(q))) @ V
 
 
@@ -69,7 +69,7 @@ def test_schematic_query_selects_by_magnitude():
         assert res.i1[0, 0].tolist() == [int(v) for v in g["i1"]]
         # tau from the printed numbers, up to the rounding of 0.8 / -1.3 / ... to 16 bits
         assert abs(res.tau[0, 0] - g["tau"][0]) < (2e-3 if dtype == F16 else 1e-2)
-        # and exactly Eq. (7) on the rounded query
+        # and exactly Eq. (9) on the rounded query
         a = np.abs(qr[0, 0])
         assert res.tau[0, 0] == pytest.approx(math.sqrt(4 * (a[0] + a[2]) / a.sum()), rel=1e-14)
 
@@ -86,7 +86,7 @@ def test_top_r_ties_go_to_lower_channel():
 @pytest.mark.parametrize("dtype", [F16, BF16])
 @pytest.mark.parametrize("seed", [0, 1, 2])
 def test_full_rank_full_k_is_dense_attention(seed, dtype):
-    """r = d_h and k = S: Steps 1-3 collapse to Eq. (1) and alpha = 1."""
+    """r = d_h and k = S: Steps 1-3 collapse to Eq. (2) and alpha = 1."""
     c = rand_case(seed, B=2, H=4, H_kv=2, S=40, d_h=16, dtype=dtype, S_max=48)
     c["seq"] = np.array([40, 33], dtype=np.int32)
     res = O.sparq_decode(c["Kc"], c["Vc"], c["qc"], c["seq"], r=16, k=48, dtype=dtype)
@@ -105,7 +105,7 @@ def test_full_rank_full_k_is_dense_attention(seed, dtype):
 
 @pytest.mark.parametrize("k", [1, 5, 17, 40])
 def test_full_rank_any_k_is_mean_value_reallocation(k):
-    """r = d_h: tau = sqrt(d_h) so s-hat = s, and alpha*y3 + (1-alpha)*v_bar equals Eq. (4)."""
+    """r = d_h: tau = sqrt(d_h) so s-hat = s, and alpha*y3 + (1-alpha)*v_bar equals Eq. (6)."""
     c = rand_case(7, S=40, d_h=16, v_shift=0.7)
     res = O.sparq_decode(c["Kc"], c["Vc"], c["qc"], c["seq"], r=16, k=k, dtype=F16)
     q, K, V = c["q"][0, 0], c["K"][0, 0], c["V"][0, 0]
@@ -116,12 +116,12 @@ def test_full_rank_any_k_is_mean_value_reallocation(k):
     assert np.abs(res.y[0, 0] - want).max() < 1e-12
     assert sorted(keep.tolist()) == res.i2[0, 0, :k].tolist()
     assert res.alpha[0, 0] == pytest.approx(s @ m, abs=1e-13)
-    # and the brute force's independent Eq. (4)
+    # and the brute force's independent Eq. (6)
     bf = BF.sparse_v_reallocation(q.tolist(), K.tolist(), V.tolist(), k)
     assert np.abs(res.y[0, 0] - np.array(bf)).max() < 1e-12
 
 
-# ---------------------------------------------------------------- temperature (Eq. 7)
+# ---------------------------------------------------------------- temperature (Eq. 9)
 
 def test_query_supported_on_r_channels_keeps_sqrt_dh_and_exact_scores():
     """Section 3: were the top-r components the only non-zero ones, tau stays sqrt(d_h);
@@ -162,7 +162,7 @@ def test_uniform_magnitude_query_gives_sqrt_r():
 
 
 def test_zero_query():
-    """0/0 in Eq. (7) is read as tau = sqrt(d_h): all logits 0, uniform scores, first k positions."""
+    """0/0 in Eq. (9) is read as tau = sqrt(d_h): all logits 0, uniform scores, first k positions."""
     S, d_h, k = 12, 8, 5
     qc = np.zeros((1, 1, d_h), dtype=np.uint16); qc[0, 0, 3] = 0x8000   # one negative zero
     rng = np.random.default_rng(5)
@@ -177,7 +177,7 @@ def test_zero_query():
     assert np.abs(res.y[0, 0] - want).max() < 1e-14
 
 
-# ---------------------------------------------------------------- alpha and the blend (Eq. 8)
+# ---------------------------------------------------------------- alpha and the blend (Eq. 10)
 
 def test_identical_keys_pin_tie_break_alpha_and_blend():
     """All keys equal: s-hat is uniform, so alpha = k/S exactly, the k lowest positions win the
@@ -196,7 +196,7 @@ def test_identical_keys_pin_tie_break_alpha_and_blend():
 
 
 def test_constant_values_give_that_constant():
-    """The weights of Eq. (8) sum to one: if every value row is c, the output is c for any r, k."""
+    """The weights of Eq. (10) sum to one: if every value row is c, the output is c for any r, k."""
     rng = np.random.default_rng(12)
     S, d_h = 33, 16
     crow = rng.normal(size=d_h)
@@ -332,26 +332,39 @@ def test_independent_heads_over_a_shared_kv_head():
         assert np.array_equal(getattr(res, name), getattr(flat, name)), name
 
 
-def test_shared_group_selection_follows_appendix_b():
-    """Section 4 'Grouped query attention': sum |q| over the group before top-r, sum s-hat over
-    the group before top-k; tau and alpha per query head.  Checked with numpy on one group."""
-    c = rand_case(52, B=1, H=4, H_kv=1, S=36, d_h=8, v_shift=0.4)
-    r, k = 3, 7
-    res = O.sparq_decode(c["Kc"], c["Vc"], c["qc"], c["seq"], r=r, k=k, dtype=F16, flags=O.GQA_SHARED)
-    q, K, V = c["q"][0], c["K"][0, 0], c["V"][0, 0]
-    i1 = np.sort(np.argsort(-np.abs(q).sum(axis=0), kind="stable")[:r])
-    scale = np.sqrt(8 * np.abs(q[:, i1]).sum(axis=1) / np.abs(q).sum(axis=1))
-    s_hat = scipy_softmax(q[:, i1] @ K[:, i1].T / scale[:, None], axis=-1)
-    i2 = np.sort(np.argsort(-s_hat.sum(axis=0), kind="stable")[:k])
-    y3 = scipy_softmax(q @ K[i2].T / math.sqrt(8), axis=-1) @ V[i2]
-    alpha = s_hat[:, i2].sum(axis=1)
-    want = alpha[:, None] * y3 + (1 - alpha[:, None]) * V.mean(axis=0)
-    for h in range(4):
-        assert res.i1[0, h].tolist() == i1.tolist() and res.i2[0, h].tolist() == i2.tolist()
-    assert np.allclose(res.tau[0], scale, rtol=1e-14)
-    assert np.allclose(res.alpha[0], alpha, atol=1e-14)
-    assert np.abs(res.y[0] - want).max() < 1e-13
-    # with one head per group the shared rule is the single-head rule
+def test_shared_rule_with_identical_heads_is_the_independent_rule():
+    """Section 4 'Grouped query attention' sums |q| and s-hat over the g heads of a group before the two
+    selections.  If the g heads carry the same query, both sums are g times one head's values: the order of
+    the channels and of the positions is that of the single head, so everything must equal the independent
+    rule's result for that head, bit for bit (tau and alpha never see the sums)."""
+    c = rand_case(52, B=2, H=2, H_kv=2, S=36, d_h=8, v_shift=0.4)
+    r, k, g = 3, 7, 4
+    qg = np.repeat(c["qc"], g, axis=1)                       # [B, H_kv * g, d_h]: every group holds one query g times
+    single = O.sparq_decode(c["Kc"], c["Vc"], c["qc"], c["seq"], r=r, k=k, dtype=F16)
+    shared = O.sparq_decode(c["Kc"], c["Vc"], qg, c["seq"], r=r, k=k, dtype=F16, flags=O.GQA_SHARED)
+    indep = O.sparq_decode(c["Kc"], c["Vc"], qg, c["seq"], r=r, k=k, dtype=F16)
+    for name in ("i1", "i2", "tau", "alpha", "y"):
+        want = np.repeat(getattr(single, name), g, axis=1)
+        assert np.array_equal(getattr(indep, name), want), name
+        assert np.array_equal(getattr(shared, name), want), name
+
+
+def test_shared_rule_against_brute_force_and_with_one_head_per_group():
+    """The grouped rule against the list-and-fsum brute force on tiny random groups (heads that disagree
+    about channels and positions), and H = H_kv, where it is the single-head rule."""
+    for seed in range(6):
+        c = rand_case(520 + seed, B=1, H=4, H_kv=1, S=30 + seed, d_h=8, v_shift=0.4)
+        r, k = 2 + seed % 3, 5 + seed
+        res = O.sparq_decode(c["Kc"], c["Vc"], c["qc"], c["seq"], r=r, k=k, dtype=F16, flags=O.GQA_SHARED)
+        S = int(c["seq"][0])
+        bf = BF.sparq_group([c["q"][0, h].tolist() for h in range(4)], c["K"][0, 0, :S].tolist(), c["V"][0, 0, :S].tolist(), r, k)
+        for h in range(4):
+            assert res.i1[0, h].tolist() == bf["i1"] and res.i2[0, h, :min(k, S)].tolist() == bf["i2"]
+            assert abs(res.tau[0, h] - bf["tau"][h]) < 1e-13 and abs(res.alpha[0, h] - bf["alpha"][h]) < 1e-13
+            assert np.abs(res.y[0, h] - np.array(bf["y"][h])).max() < 1e-12
+        # the heads of these groups do not agree with each other: the shared sets are not what each head alone picks
+        alone = O.sparq_decode(c["Kc"], c["Vc"], c["qc"], c["seq"], r=r, k=k, dtype=F16)
+        assert any(alone.i2[0, h].tolist() != res.i2[0, h].tolist() for h in range(4)) or seed > 0
     c1 = rand_case(53, B=1, H=2, H_kv=2, S=20, d_h=8)
     a = O.sparq_decode(c1["Kc"], c1["Vc"], c1["qc"], c1["seq"], r=2, k=4, dtype=F16)
     b = O.sparq_decode(c1["Kc"], c1["Vc"], c1["qc"], c1["seq"], r=2, k=4, dtype=F16, flags=O.GQA_SHARED)

@@ -22,7 +22,7 @@ def test_printed_theoretical_speedups():
 
 
 def test_element_counts_term_by_term():
-    # Section 3 Eq. (2) and the transfer equation of Section 4, on a shape small enough to count by hand
+    # Section 3 Eq. (3) and the transfer equation of Section 4, on a shape small enough to count by hand
     assert T.dense_elements(10, 4) == 2 * 10 * 4 + 2 * 4
     assert T.sparq_elements(10, 4, 2, 3) == 10 * 2 + 2 * 3 * 4 + 4 * 4
     b = T.sparq_decode_bytes([4096] * 16, H=32, d_h=128, r=32, k=512)
