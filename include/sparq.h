@@ -52,7 +52,8 @@ typedef enum {
   SPARQ_EINVAL = -1,       /* null / misaligned pointer, inconsistent shape */
   SPARQ_EUNSUPPORTED = -2, /* valid request this build has no kernel for */
   SPARQ_EWORKSPACE = -3,   /* workspace missing or smaller than sparq_workspace_bytes */
-  SPARQ_ELAUNCH = -4       /* the HIP runtime refused the launch */
+  SPARQ_ELAUNCH = -4,      /* the HIP runtime refused the launch */
+  SPARQ_ETOOLARGE = -5     /* sparq_decode_noalloc: the shape needs more scratch than the built-in buffer */
 } sparq_status;
 
 typedef enum { SPARQ_F16 = 0, SPARQ_BF16 = 1 } sparq_dtype;
@@ -166,6 +167,25 @@ int sparq_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
                  const int32_t* k_per_seq, void* out, float* alpha_out, int32_t* idx_out,
                  int32_t idx_stride, int32_t* chan_out, void* workspace,
                  size_t workspace_bytes, void* hip_stream);
+
+/*
+ * sparq_decode for callers that cannot allocate or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same computation, same kernels and same results
+ * as sparq_decode; the scratch that call takes from `workspace` (partials, keys, candidates and position
+ * lists of the multi-launch plans, the logits of the grouped-query rule) comes from a buffer built into the
+ * library instead: 32 MiB of device memory per GPU, held from the first call on that GPU until the process
+ * ends.  The call allocates nothing and frees nothing (its first call on a device looks up the buffer's
+ * address and enqueues one small fill kernel on `hip_stream`).
+ *   error_word  device int32 or NULL: the SPARQ_ERR_* bits of this call are OR-ed into it (the caller
+ *               clears and reads it); with NULL they are dropped
+ * Shapes for which sparq_workspace_bytes exceeds 32 MiB return SPARQ_ETOOLARGE before any launch.
+ * All calls on one GPU share the one buffer: two calls that may run at the same time on one GPU (different
+ * streams, or graphs replayed concurrently) race on it and must be ordered by the caller.  Nothing in the
+ * buffer has to survive between calls.  Other arguments as for sparq_decode.
+ */
+int sparq_decode_noalloc(const sparq_shape* shape, const sparq_cache* cache, const void* q,
+                         const int32_t* k_per_seq, void* out, float* alpha_out, int32_t* idx_out,
+                         int32_t idx_stride, int32_t* chan_out, int32_t* error_word, void* hip_stream);
 
 /*
  * The whole decode step in one launch: exactly sparq_kv_append with n_new = 1 followed by

@@ -19,9 +19,9 @@ SPARQ_F16, SPARQ_BF16 = 0, 1
 SPARQ_FLAG_NO_REALLOC, SPARQ_FLAG_GQA_SHARED, SPARQ_FLAG_RAGGED_BATCH = 1, 2, 4
 SPARQ_FLAG_TAU_SQRT_DH, SPARQ_FLAG_TAU_SQRT_R, SPARQ_FLAG_SINGLE_K = 8, 16, 32
 SPARQ_ERR_APPEND_FULL, SPARQ_ERR_EMPTY_SEQ, SPARQ_ERR_IDX_TRUNCATED, SPARQ_ERR_BAD_SEQ_LEN = 1, 2, 4, 8
-SPARQ_OK, SPARQ_EINVAL, SPARQ_EUNSUPPORTED, SPARQ_EWORKSPACE, SPARQ_ELAUNCH = 0, -1, -2, -3, -4
+SPARQ_OK, SPARQ_EINVAL, SPARQ_EUNSUPPORTED, SPARQ_EWORKSPACE, SPARQ_ELAUNCH, SPARQ_ETOOLARGE = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ["sparq_workspace_bytes", "sparq_workspace_init", "sparq_kv_append", "sparq_decode", "sparq_decode_step",
+EXPORTS = ["sparq_workspace_bytes", "sparq_workspace_init", "sparq_kv_append", "sparq_decode", "sparq_decode_noalloc", "sparq_decode_step",
            "dense_decode", "sparq_async_error", "sparq_copy_probe", "sparq_read_probe", "sparq_decode_plan",
            "sparq_status_string"]
 
@@ -62,6 +62,7 @@ def load() -> ctypes.CDLL:
     L.sparq_workspace_init.argtypes = [vp, sz, vp]
     L.sparq_kv_append.argtypes = [shp, cch, vp, vp, i32, vp, vp, sz, vp]
     L.sparq_decode.argtypes = [shp, cch, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+    L.sparq_decode_noalloc.argtypes = [shp, cch, vp, vp, vp, vp, vp, i32, vp, vp, vp]
     L.sparq_decode_step.argtypes = [shp, cch, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
     L.dense_decode.argtypes = [shp, cch, vp, vp, vp, sz, vp]
     L.sparq_async_error.argtypes = [vp, ctypes.POINTER(i32), vp]
@@ -147,6 +148,17 @@ def sparq_decode(shape, cache, q, k_per_seq, out, alpha_out, idx_out, chan_out, 
                                idx_stride, _dev(chan_out, "chan_out", torch.int32),
                                _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                _stream(stream)))
+
+
+def sparq_decode_noalloc(shape, cache, q, k_per_seq, out, alpha_out, idx_out, chan_out, error_word=None, stream=None) -> None:
+    """sparq_decode on the library's built-in scratch buffer (no workspace argument, nothing allocated)."""
+    idx_stride = 0 if idx_out is None else idx_out.shape[-1]
+    _check("sparq_decode_noalloc",
+           load().sparq_decode_noalloc(ctypes.byref(shape), ctypes.byref(cache), _dev(q, "q"),
+                                       _dev(k_per_seq, "k_per_seq", torch.int32), _dev(out, "out"),
+                                       _dev(alpha_out, "alpha_out", torch.float32), _dev(idx_out, "idx_out", torch.int32),
+                                       idx_stride, _dev(chan_out, "chan_out", torch.int32),
+                                       _dev(error_word, "error_word", torch.int32), _stream(stream)))
 
 
 def sparq_decode_step(shape, cache, k_new, v_new, v_mean_next, seq_lens_next, q, k_per_seq, out, alpha_out,

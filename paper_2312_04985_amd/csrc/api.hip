@@ -313,6 +313,29 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
 
 bool decode_supported(const sparq_shape* shape) { return choose_plan(shape).plan != kPlanNone; }
 
+// ---- library-owned scratch for sparq_decode_noalloc ----
+// One array per GPU (each device that loads this code object holds its own copy at its own address), kept
+// until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: kernels,
+// fills and copies take the device address looked up below, never the name.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device; looked up (and the control block cleared by a fill
+// kernel on `s`) on the first call per device.  Returns nullptr if the runtime refuses.
+void* static_scratch(hipStream_t s) {
+  static void* ptr[kMaxDevices] = {};      // benign race: every thread computes the same value
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    if (launch_clear(p, kControlBytes, s) != hipSuccess) return nullptr;
+    ptr[dev] = p;
+  }
+  return ptr[dev];
+}
+
 }  // namespace
 
 extern "C" {
@@ -368,6 +391,30 @@ int sparq_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
   a.r = shape->r; a.k = shape->k; a.idx_stride = idx_out ? idx_stride : 0; a.flags = shape->flags;
   a.local_window = shape->local_window;
   return enqueue_decode(shape, a, workspace, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
+}
+
+int sparq_decode_noalloc(const sparq_shape* shape, const sparq_cache* cache, const void* q,
+                         const int32_t* k_per_seq, void* out, float* alpha_out, int32_t* idx_out,
+                         int32_t idx_stride, int32_t* chan_out, int32_t* error_word, void* hip_stream) {
+  int rc = check_shape(shape);
+  if (rc == SPARQ_OK) rc = check_cache(cache, shape);
+  if (rc != SPARQ_OK) return rc;
+  if (!q || !out || !aligned16(q) || !aligned16(out)) return SPARQ_EINVAL;
+  if (idx_out && idx_stride < 1) return SPARQ_EINVAL;
+  if (!decode_supported(shape)) return SPARQ_EUNSUPPORTED;
+  if (workspace_need(shape) > kStaticScratchBytes) return SPARQ_ETOOLARGE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  void* ws = static_scratch(s);
+  if (!ws) return SPARQ_ELAUNCH;
+  DecodeArgs a;
+  a.K = cache->K; a.Kt = cache->Kt; a.V = cache->V; a.v_mean = cache->v_mean; a.seq_lens = cache->seq_lens;
+  a.q = q; a.k_per_seq = k_per_seq; a.out = out; a.alpha_out = alpha_out; a.idx_out = idx_out;
+  a.k_new = nullptr; a.v_new = nullptr; a.v_mean_next = nullptr; a.seq_lens_next = nullptr;
+  a.chan_out = chan_out; a.err = error_word ? error_word : static_cast<int32_t*>(ws);
+  a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h;
+  a.r = shape->r; a.k = shape->k; a.idx_stride = idx_out ? idx_stride : 0; a.flags = shape->flags;
+  a.local_window = shape->local_window;
+  return enqueue_decode(shape, a, ws, s) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
 int sparq_decode_step(const sparq_shape* shape, const sparq_cache* cache, const void* k_new,
@@ -453,6 +500,7 @@ const char* sparq_status_string(int status) {
     case SPARQ_EUNSUPPORTED: return "unsupported shape or mode";
     case SPARQ_EWORKSPACE: return "workspace missing, misaligned or too small";
     case SPARQ_ELAUNCH: return "HIP launch failed";
+    case SPARQ_ETOOLARGE: return "shape needs more scratch than the library's built-in buffer holds";
     default: return "unknown status";
   }
 }
