@@ -87,7 +87,8 @@ enum {
   SPARQ_ERR_APPEND_FULL = 1,   /* an append would pass S_max: that sequence was skipped */
   SPARQ_ERR_EMPTY_SEQ = 2,     /* decode of a sequence with S_b = 0: zeros written */
   SPARQ_ERR_IDX_TRUNCATED = 4, /* min(k_b, S_b) exceeded idx_stride: idx_out truncated */
-  SPARQ_ERR_BAD_SEQ_LEN = 8    /* seq_lens[b] outside [0, S_max]: clamped */
+  SPARQ_ERR_BAD_SEQ_LEN = 8,   /* seq_lens[b] outside [0, S_max]: clamped */
+  SPARQ_ERR_INTERNAL = 16      /* a consistency check inside a kernel failed (a defect of the library): results invalid */
 };
 
 typedef struct {

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsparq.so")
-SOURCES = ["api.hip", "sparq_decode.hip", "sparq_decode_split.hip", "sparq_decode_shared.hip", "sparq_decode_shared_split.hip", "sparq_decode_single_k.hip", "sparq_decode_long.hip", "dense_decode.hip", "kv_append.hip"]
+SOURCES = ["api.hip", "sparq_decode.hip", "sparq_decode_split.hip", "sparq_decode_shared.hip", "sparq_decode_shared_split.hip", "sparq_decode_single_k.hip", "sparq_decode_long.hip", "sparq_decode_bucket.hip", "dense_decode.hip", "kv_append.hip"]
 HEADERS = ["common.h", "params.h", "decode_stages.h", "group_stages.h", os.path.join("..", "..", "include", "sparq.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -28,7 +28,7 @@ class DecodeCache:
         self.V = mk((Bsz, H_kv, S_max, d_h), dtype=dtype, device=self.device)
         self.v_mean = torch.zeros((Bsz, H_kv, d_h), dtype=torch.float32, device=self.device)
         self.seq_lens = torch.zeros((Bsz,), dtype=torch.int32, device=self.device)
-        self.workspace = torch.empty((B.sparq_workspace_bytes(self.shape),), dtype=torch.uint8, device=self.device)
+        self.workspace = torch.zeros((B.sparq_workspace_bytes(self.shape),), dtype=torch.uint8, device=self.device)
         B.sparq_workspace_init(self.workspace)
         self.cache = B.make_cache(self.K, self.Kt, self.V, self.v_mean, self.seq_lens)
         self._v_mean_alt = None      # second (v_mean, seq_lens) pair for the one-launch step, made on first use
@@ -40,7 +40,7 @@ class DecodeCache:
         self.shape = B.make_shape(self.B, self.H, self.H_kv, self.S_max, self.d_h, r, k, self.dtype, flags, local_window)
         need = B.sparq_workspace_bytes(self.shape)          # the plan, and with it the scratch size, may change
         if need > self.workspace.numel():
-            self.workspace = torch.empty((need,), dtype=torch.uint8, device=self.device)
+            self.workspace = torch.zeros((need,), dtype=torch.uint8, device=self.device)
             B.sparq_workspace_init(self.workspace)
         return self
 

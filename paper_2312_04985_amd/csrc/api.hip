@@ -107,7 +107,7 @@ bool single_k(const sparq_shape* shape) { return (shape->flags & SPARQ_FLAG_SING
 
 // Which kernels serve a shape.  Every plan keeps one 4-byte key per position (or per candidate) of its
 // unit of work in LDS; that decides what fits.
-enum Plan { kPlanNone, kPlanFused, kPlanSplit, kPlanLong, kPlanShared, kPlanSharedSplit, kPlanSingleK };
+enum Plan { kPlanNone, kPlanFused, kPlanSplit, kPlanLong, kPlanShared, kPlanSharedSplit, kPlanSingleK, kPlanBucket };
 struct PlanInfo { Plan plan; int n_split, n_span, span_len, cand_cap, n1, span1; };
 
 // The two-level plan: spans of `span` positions select their own top-k, one workgroup per unit merges at
@@ -126,6 +126,29 @@ bool two_level_plan(const sparq_shape* s, int span, size_t lds_max, PlanInfo* p)
   if (n > s->k / 64) n = s->k / 64;
   if (n < 1) n = 1;
   p->n_span = (int)n_span; p->span_len = span; p->cand_cap = cap; p->n_split = (int)n;
+  return true;
+}
+
+// The digit-bucket plan for few units with long caches: about 512 workgroups in all, spans of 1024 to 8192
+// positions (a multiple of 64), at most kMaxSpans of them.
+bool bucket_plan(const sparq_shape* s, size_t lds_max, PlanInfo* p) {
+  const int64_t units = (int64_t)s->B * s->H;
+  int64_t n_span = 512 / units;
+  if (n_span < 2) n_span = 2;
+  // (units x n_span <= 512: both kernels hold two workgroups per CU, and a second round of workgroups costs
+  // more than longer spans do)
+  if (n_span > kMaxSpans) n_span = kMaxSpans;
+  int64_t span = (s->S_max + n_span - 1) / n_span;
+  if (span < 1024) span = 1024;
+  span = (span + 63) / 64 * 64;
+  if (span > kLongSpan) span = kLongSpan;
+  n_span = (s->S_max + span - 1) / span;
+  if (n_span > kMaxSpans) return false;
+  // the keys that share the threshold digit are a few percent of the sequence unless many keys are identical
+  const int cap = s->S_max <= 40000 ? 2048 : (s->S_max <= 100000 ? 4096 : 8192);
+  if (bk_scores_lds_bytes((int)span, s->d_h) > lds_max ||
+      bk_select_lds_bytes((int)span, s->d_h, (int)n_span, cap) > lds_max) return false;
+  p->n_span = (int)n_span; p->span_len = (int)span; p->cand_cap = cap;
   return true;
 }
 
@@ -173,6 +196,7 @@ PlanInfo choose_plan(const sparq_shape* s) {
     if (one_wg) p.plan = kPlanShared;
     return p;
   }
+  if ((int64_t)s->B * s->H <= kSplitMaxUnits && s->S_max >= 8192 && bucket_plan(s, lds_max, &p)) { p.plan = kPlanBucket; return p; }
   if ((int64_t)s->B * s->H <= kSplitMaxUnits && s->S_max >= 16384) {
     const int span = s->S_max >= 32768 ? kLongSpan : kLongSpan / 2;
     if (s->k < span && two_level_plan(s, span, lds_max, &p)) { p.plan = kPlanLong; return p; }
@@ -204,6 +228,26 @@ GsLayout gs_layout(const sparq_shape* s, const PlanInfo& p) {
   return l;
 }
 
+struct BucketLayout { size_t tmax, zsum, anum, tau, zden, coarse, fine, skey, spos, part, end; };
+
+BucketLayout bucket_layout(const sparq_shape* s, const PlanInfo& p) {
+  const size_t units = (size_t)s->B * s->H, slots = units * p.n_span;
+  BucketLayout l;
+  size_t off = kControlBytes;
+  l.tmax = off; off = align256(off + slots * sizeof(float));
+  l.zsum = off; off = align256(off + slots * sizeof(float));
+  l.anum = off; off = align256(off + slots * sizeof(float));
+  l.tau = off; off = align256(off + units * sizeof(float));
+  l.zden = off; off = align256(off + units * sizeof(float));
+  l.coarse = off; off = align256(off + slots * 64 * sizeof(uint16_t));
+  l.fine = off; off = align256(off + slots * bk_fine_len() * sizeof(uint16_t));
+  l.skey = off; off = align256(off + slots * p.span_len * sizeof(uint32_t));
+  l.spos = off; off = align256(off + slots * p.span_len * sizeof(uint32_t));
+  l.part = off; off = align256(off + slots * (s->d_h + 2) * sizeof(float));
+  l.end = off;
+  return l;
+}
+
 struct LongLayout { size_t tmax, zsum, cnt, tau, alpha, ckey, cpos, list, part, end; };
 
 LongLayout long_layout(const sparq_shape* s, const PlanInfo& p) {
@@ -231,6 +275,7 @@ size_t workspace_need(const sparq_shape* s) {
   size_t e = 0;
   if (p.plan == kPlanSplit) e = split_layout(s, p.n_split).end;
   if (p.plan == kPlanLong) e = long_layout(s, p).end;
+  if (p.plan == kPlanBucket) e = bucket_layout(s, p).end;
   if (p.plan == kPlanShared) e = (size_t)kControlBytes + (size_t)s->B * s->H * s->S_max * sizeof(float);
   if (p.plan == kPlanSharedSplit) e = gs_layout(s, p).end;
   return e > need ? e : need;
@@ -281,6 +326,23 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
     ga.list_ws = reinterpret_cast<int32_t*>(w + l.list);
     ga.part_ws = reinterpret_cast<float*>(w + l.part);
     return launch_decode_shared_split(ga, shape->dtype, s);
+  }
+  if (p.plan == kPlanBucket) {
+    const BucketLayout l = bucket_layout(shape, p);
+    BucketArgs ba;
+    ba.d = d;
+    ba.n_span = p.n_span; ba.span_len = p.span_len; ba.cand_cap = p.cand_cap;
+    ba.tmax_ws = reinterpret_cast<float*>(w + l.tmax);
+    ba.zsum_ws = reinterpret_cast<float*>(w + l.zsum);
+    ba.anum_ws = reinterpret_cast<float*>(w + l.anum);
+    ba.tau_ws = reinterpret_cast<float*>(w + l.tau);
+    ba.zden_ws = reinterpret_cast<float*>(w + l.zden);
+    ba.coarse_ws = reinterpret_cast<uint16_t*>(w + l.coarse);
+    ba.fine_ws = reinterpret_cast<uint16_t*>(w + l.fine);
+    ba.skey_ws = reinterpret_cast<uint32_t*>(w + l.skey);
+    ba.spos_ws = reinterpret_cast<uint32_t*>(w + l.spos);
+    ba.part_ws = reinterpret_cast<float*>(w + l.part);
+    return launch_decode_bucket(ba, shape->dtype, s);
   }
   if (p.plan == kPlanLong) {
     const LongLayout l = long_layout(shape, p);
@@ -486,6 +548,7 @@ const char* sparq_decode_plan(const sparq_shape* shape) {
     case kPlanFused: return "sparq_decode_fused (one workgroup per head, one launch)";
     case kPlanSplit: return "split_scores + split_select + split_gather + split_combine (split-sequence plan)";
     case kPlanLong: return "long_scores + long_merge + split_gather + split_combine (two-level selection plan)";
+    case kPlanBucket: return "bk_scores + bk_select_gather + bk_combine (digit-bucket plan)";
     case kPlanShared: return "sparq_decode_shared (grouped-query rule, one workgroup per KV head)";
     case kPlanSharedSplit: return "gs_logits + gs_select + gs_merge + gs_gather + split_combine (grouped-query rule, several workgroups per KV head)";
     case kPlanSingleK: return "sparq_decode_single_k (key cache stored once)";

@@ -171,23 +171,24 @@ __device__ __forceinline__ Window make_window(int local_window, int S, int kq) {
 // ------------------------------------------------------------------------------------------------
 // Step 1b: approximate logit numerators over the r selected rows of the S-contiguous key copy
 
-// Chunks (8 consecutive positions = 16 bytes of every channel row) chunk_begin + tid + i * NT belong to
-// thread tid.  The (chunk, batch-of-8-rows) pairs a thread owns form one flat sequence that runs through
+// Chunks (8 consecutive positions = 16 bytes of every channel row) chunk_begin + tid + i * STRIDE belong to
+// thread tid of STRIDE (all NT threads of the workgroup unless the caller divides the rows of a chunk among
+// groups of threads).  The (chunk, batch-of-8-rows) pairs a thread owns form one flat sequence that runs through
 // a two-deep software pipeline: a batch of 8 loads is always in flight behind the one being accumulated,
 // also across chunk boundaries.  fp32 FMA in ascending channel order.  finish(c, acc) is called with the
 // 8 sums of chunk c.  No barrier.
-template <class T, class Finish>
+template <class T, int STRIDE = NT, class Finish>
 __device__ __forceinline__ void stream_channel_rows(const char* Kt_head, size_t row_bytes, const int* chan,
                                                     const float* qs, int r, int chunk_begin, int chunk_end,
                                                     int tid, Finish&& finish) {
   const int n_batches = (r + 7) >> 3;
   const int n_chunks = chunk_end - chunk_begin;
-  const int my_chunks = n_chunks > tid ? (n_chunks - tid + NT - 1) / NT : 0;
+  const int my_chunks = n_chunks > tid ? (n_chunks - tid + STRIDE - 1) / STRIDE : 0;
   const int items = my_chunks * n_batches;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   int ic = 0, ib = 0, cc = 0, cb = 0;   // issue and consume cursors: (own chunk number, batch)
   auto issue_next = [&](uint4 (&v)[8]) {
-    const uint32_t voff = (uint32_t)(chunk_begin + tid + ic * NT) * 16u;
+    const uint32_t voff = (uint32_t)(chunk_begin + tid + ic * STRIDE) * 16u;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       const int ch = __builtin_amdgcn_readfirstlane(chan[ib * 8 + t]);   // uniform: scalar row base
@@ -205,7 +206,7 @@ __device__ __forceinline__ void stream_channel_rows(const char* Kt_head, size_t 
       for (int e = 0; e < 8; ++e) acc[e] = fmaf(f[e], qv, acc[e]);
     }
     if (++cb == n_batches) {
-      finish(chunk_begin + tid + cc * NT, acc);
+      finish(chunk_begin + tid + cc * STRIDE, acc);
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
       cb = 0; ++cc;

@@ -92,6 +92,23 @@ struct SplitArgs {
   float* part_ws;        // [B * H][n_split][d_h + 2] attention partials
 };
 
+// digit-bucket plan (few units, long caches): spans of span_len positions, n_span of them per unit
+struct BucketArgs {
+  DecodeArgs d;
+  int32_t n_span, span_len;
+  int32_t cand_cap;        // candidates (keys sharing the threshold digit) that bk_select_gather ranks out of LDS
+  float* tmax_ws;          // [B * H][n_span] largest logit numerator of each span
+  float* zsum_ws;          // [B * H][n_span] sum over the span of exp((d - span max) / tau)
+  float* anum_ws;          // [B * H][n_span] the span's share of alpha's numerator (relative to the sequence maximum)
+  float* tau_ws;           // [B * H]
+  float* zden_ws;          // [B * H] softmax denominator of the approximate scores
+  uint16_t* coarse_ws;     // [B * H][n_span][64] A[32 l]
+  uint16_t* fine_ws;       // [B * H][n_span][2080] A[d] = keys of the span with first digit >= d
+  uint32_t* skey_ws;       // [B * H][n_span][span_len] the span's keys sorted by first digit, descending
+  uint32_t* spos_ws;       // [B * H][n_span][span_len] their positions
+  float* part_ws;          // [B * H][n_span][d_h + 2] attention partials of the spans
+};
+
 // LDS bytes the fused decode kernel needs for a cache of S_max rows and head dimension d_h
 size_t decode_lds_bytes(int S_max, int d_h);
 size_t split_select_lds_bytes(int S_max);
@@ -103,6 +120,10 @@ hipError_t launch_decode_single_k(const DecodeArgs& a, int dtype, hipStream_t s)
 size_t long_scores_lds_bytes(int span_len, int d_h);
 size_t long_merge_lds_bytes(int n_span, int cand_cap);
 hipError_t launch_decode_long(const LongArgs& a, int dtype, hipStream_t s);
+size_t bk_scores_lds_bytes(int span_len, int d_h);
+size_t bk_select_lds_bytes(int span_len, int d_h, int n_span, int cand_cap);
+int bk_fine_len();
+hipError_t launch_decode_bucket(const BucketArgs& a, int dtype, hipStream_t s);
 // the last two launches of the split-sequence plan (gather over slices of list_ws, merge): uses d, n_split,
 // alpha_ws, list_ws, part_ws of `a`
 hipError_t launch_split_gather(const SplitArgs& a, int dtype, hipStream_t s);
