@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-others", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--layout", choices=["two_copies", "single_k", "tiled_k"], default="two_copies",
+                    help="key cache layout: K twice (default), once row-major (SPARQ_FLAG_SINGLE_K), once in tiles (SPARQ_FLAG_TILED_K)")
     return ap.parse_args()
 
 
@@ -106,12 +108,13 @@ def measure(name, K, Wm, args, full):
     per_copy = -(-max(K, Wm, pre) // copies) + 1     # appends one copy receives in one pass
     S_max = W.round_up(int(seq0.max()) + per_copy, 64)
 
+    layout_flag = {"two_copies": 0, "single_k": B.SPARQ_FLAG_SINGLE_K, "tiled_k": B.SPARQ_FLAG_TILED_K}[args.layout]
     # ---- build the caches through the library (bulk append of S_b - 1 rows) ----
     K_src, V_src = W.draw_kv(w, dev, n_rows=int(seq0.max()))
     caches = []
     for _ in range(copies):
         c = DecodeCache(w.B, w.H, w.H_kv, S_max, w.d_h, w.r, w.k, w.torch_dtype, device=dev,
-                        flags=B.SPARQ_FLAG_RAGGED_BATCH if w.ragged else 0)
+                        flags=(B.SPARQ_FLAG_RAGGED_BATCH if w.ragged else 0) | layout_flag)
         c.append(K_src, V_src, (seq0 - 1).to(dev))
         caches.append(c)
     torch.cuda.synchronize()
@@ -245,7 +248,7 @@ def measure(name, K, Wm, args, full):
         "workload": name, "ms_per_step": ms_per_step, "steps_per_s": 1e3 / ms_per_step, "plan": plan,
         "config": {"workload": name, "B": w.B, "H": w.H, "H_kv": w.H_kv, "d_h": w.d_h, "S": int(seq0.max()),
                    "r": w.r, "k": w.k if kps is None else "ceil(S_b/%d)" % w.k_div, "cache_dtype": w.dtype,
-                   "step": "sparq_decode_step (append + decode in one call)", "cache_copies_rotated": copies,
+                   "step": "sparq_decode_step (append + decode in one call)", "key_layout": args.layout, "cache_copies_rotated": copies,
                    "q_pool": n_pool, "S_max": S_max, "untimed_clock_warmup_steps": pre},
         "step_GBps": round((dec_bytes + app_bytes) / ms_per_step / 1e6, 1),
         "step_frac_of_peak": round((dec_bytes + app_bytes) / ms_per_step / 1e6 / HBM_PEAK_GBS, 4),
@@ -263,7 +266,7 @@ def measure(name, K, Wm, args, full):
     }
 
     # ---- in-library dense decode on the same rotation ----
-    if not args.no_dense:
+    if not args.no_dense and args.layout != "tiled_k":   # the comparison kernel reads key rows
         dense_fn = lambda i: check(lib.dense_decode(*table[i % copies][0][i % n_pool]["dense"]))
         for i in range(min(Wm, 5)):
             dense_fn(i)
@@ -305,7 +308,7 @@ def measure(name, K, Wm, args, full):
         kq_max = int(torch.minimum(kps if kps is not None else torch.full_like(seq0, w.k), seq0).max())
         got_t, _, idx_t, _ = c.decode(q_pool[0], kps_dev, aux=True, idx_stride=kq_max)
         torch.cuda.synchronize()
-        Kh = W.to_codes(c.K); Vh = W.to_codes(c.V); qh = W.to_codes(q_pool[0])
+        Kh = W.to_codes(c.key_rows()); Vh = W.to_codes(c.V); qh = W.to_codes(q_pool[0])
         seq_h = c.seq_lens.cpu().numpy(); kk_h = None if kps is None else kps.numpy()
         reps, spent = 0, 0.0
         while spent < args.cpu_seconds and reps < 50:

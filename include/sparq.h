@@ -79,7 +79,17 @@ enum {
   /* the key cache is stored once, d_h-contiguous only (the "1 x K" variant of Section 6.1): cache.Kt
    * is ignored and may be null, sparq_kv_append writes no second copy, and Step 1 reads the rows of K
    * whole (S d_h elements instead of S r).  Not combined with SPARQ_FLAG_GQA_SHARED. */
-  SPARQ_FLAG_SINGLE_K = 1u << 5
+  SPARQ_FLAG_SINGLE_K = 1u << 5,
+  /* the key cache is stored once in a layout that serves both steps (Section 6.1 closes by asking for
+   * alternatives to storing K twice): tiles of 8 positions, channel-major inside a tile.  cache.K is then
+   * [B, H_kv, S_max / 8, d_h, 8] (element (position p, channel j) at ((p / 8) d_h + j) 8 + p % 8: the same
+   * number of bytes as the row-major K) and cache.Kt is a small buffer [B, H_kv, 8, d_h] holding the rows of
+   * the positions 8 floor(S_b / 8) .. S_b - 1, which move into their tile, as one contiguous block, when the
+   * eighth arrives.  Step 1 reads 16 bytes per selected channel and group of 8 positions (2 d_h bytes apart),
+   * Step 2 collects a key row's components from its tile.  Served by the one-workgroup-per-head kernel
+   * (S_max up to about 35 000); dense_decode, SPARQ_FLAG_GQA_SHARED and SPARQ_FLAG_SINGLE_K are not combined
+   * with it (SPARQ_EUNSUPPORTED / SPARQ_EINVAL). */
+  SPARQ_FLAG_TILED_K = 1u << 6
 };
 
 /* bits of the device-side error word (sparq_async_error) */

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "libsparq.so")
 
 SPARQ_F16, SPARQ_BF16 = 0, 1
 SPARQ_FLAG_NO_REALLOC, SPARQ_FLAG_GQA_SHARED, SPARQ_FLAG_RAGGED_BATCH = 1, 2, 4
-SPARQ_FLAG_TAU_SQRT_DH, SPARQ_FLAG_TAU_SQRT_R, SPARQ_FLAG_SINGLE_K = 8, 16, 32
+SPARQ_FLAG_TAU_SQRT_DH, SPARQ_FLAG_TAU_SQRT_R, SPARQ_FLAG_SINGLE_K, SPARQ_FLAG_TILED_K = 8, 16, 32, 64
 SPARQ_ERR_APPEND_FULL, SPARQ_ERR_EMPTY_SEQ, SPARQ_ERR_IDX_TRUNCATED, SPARQ_ERR_BAD_SEQ_LEN, SPARQ_ERR_INTERNAL = 1, 2, 4, 8, 16
 SPARQ_OK, SPARQ_EINVAL, SPARQ_EUNSUPPORTED, SPARQ_EWORKSPACE, SPARQ_ELAUNCH, SPARQ_ETOOLARGE = 0, -1, -2, -3, -4, -5
 

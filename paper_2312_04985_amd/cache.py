@@ -22,9 +22,15 @@ class DecodeCache:
         self.dtype, self.device = dtype, torch.device(device)
         self.shape = B.make_shape(Bsz, H, H_kv, S_max, d_h, r, k, dtype, flags)
         mk = torch.zeros if poison is None else (lambda *a, **kw: torch.full(*a, fill_value=poison, **kw))
-        self.K = mk((Bsz, H_kv, S_max, d_h), dtype=dtype, device=self.device)
-        # with SPARQ_FLAG_SINGLE_K at construction there is no second key copy at all
-        self.Kt = None if flags & B.SPARQ_FLAG_SINGLE_K else mk((Bsz, H_kv, d_h, S_max), dtype=dtype, device=self.device)
+        self.tiled = bool(flags & B.SPARQ_FLAG_TILED_K)
+        if self.tiled:
+            # one key copy in tiles of 8 positions (channel-major inside a tile) + the rows that wait for their tile
+            self.K = mk((Bsz, H_kv, S_max // 8, d_h, 8), dtype=dtype, device=self.device)
+            self.Kt = mk((Bsz, H_kv, 8, d_h), dtype=dtype, device=self.device)
+        else:
+            self.K = mk((Bsz, H_kv, S_max, d_h), dtype=dtype, device=self.device)
+            # with SPARQ_FLAG_SINGLE_K at construction there is no second key copy at all
+            self.Kt = None if flags & B.SPARQ_FLAG_SINGLE_K else mk((Bsz, H_kv, d_h, S_max), dtype=dtype, device=self.device)
         self.V = mk((Bsz, H_kv, S_max, d_h), dtype=dtype, device=self.device)
         self.v_mean = torch.zeros((Bsz, H_kv, d_h), dtype=torch.float32, device=self.device)
         self.seq_lens = torch.zeros((Bsz,), dtype=torch.int32, device=self.device)
@@ -87,6 +93,19 @@ class DecodeCache:
         out = torch.empty((self.B, self.H, self.d_h), dtype=self.dtype, device=self.device) if out is None else out
         B.dense_decode(self.shape, self.cache, q, out, self.workspace, stream)
         return out
+
+    def key_rows(self) -> torch.Tensor:
+        """The cached keys as rows [B, H_kv, S_max, d_h], whatever the layout (a copy for the tiled layout: tiles
+        un-tiled, the rows still waiting for their tile taken from the small buffer; bookkeeping for tests)."""
+        if not self.tiled:
+            return self.K
+        rows = self.K.permute(0, 1, 2, 4, 3).reshape(self.B, self.H_kv, self.S_max, self.d_h).clone()
+        lens = self.seq_lens.cpu().tolist()
+        for b, s in enumerate(lens):
+            fl = s & ~7
+            if s > fl:
+                rows[b, :, fl:s] = self.Kt[b, :, :s - fl]
+        return rows
 
     def error_flags(self) -> int:
         return B.sparq_async_error(self.workspace)

@@ -21,7 +21,8 @@ int check_shape(const sparq_shape* s) {
   if (s->dtype != SPARQ_F16 && s->dtype != SPARQ_BF16) return SPARQ_EINVAL;
   if (s->S_max % 64 != 0) return SPARQ_EINVAL;
   if (s->flags & ~(uint32_t)(SPARQ_FLAG_NO_REALLOC | SPARQ_FLAG_GQA_SHARED | SPARQ_FLAG_RAGGED_BATCH |
-                             SPARQ_FLAG_TAU_SQRT_DH | SPARQ_FLAG_TAU_SQRT_R | SPARQ_FLAG_SINGLE_K)) return SPARQ_EINVAL;
+                             SPARQ_FLAG_TAU_SQRT_DH | SPARQ_FLAG_TAU_SQRT_R | SPARQ_FLAG_SINGLE_K | SPARQ_FLAG_TILED_K)) return SPARQ_EINVAL;
+  if ((s->flags & SPARQ_FLAG_SINGLE_K) && (s->flags & SPARQ_FLAG_TILED_K)) return SPARQ_EINVAL;
   if ((s->flags & SPARQ_FLAG_TAU_SQRT_DH) && (s->flags & SPARQ_FLAG_TAU_SQRT_R)) return SPARQ_EINVAL;
   if (s->local_window < 0) return SPARQ_EINVAL;
   if (s->d_h != 64 && s->d_h != 128 && s->d_h != 256) return SPARQ_EUNSUPPORTED;
@@ -104,6 +105,7 @@ bool wants_shared(const sparq_shape* shape) {
 }
 
 bool single_k(const sparq_shape* shape) { return (shape->flags & SPARQ_FLAG_SINGLE_K) != 0; }
+bool tiled_k(const sparq_shape* shape) { return (shape->flags & SPARQ_FLAG_TILED_K) != 0; }
 
 // Which kernels serve a shape.  Every plan keeps one 4-byte key per position (or per candidate) of its
 // unit of work in LDS; that decides what fits.
@@ -182,6 +184,10 @@ PlanInfo choose_plan(const sparq_shape* s) {
   if (single_k(s)) {
     const size_t need = wants_shared(s) ? 0 : decode_single_k_lds_bytes(s->S_max, s->d_h);
     if (need != 0 && need <= lds_max) p.plan = kPlanSingleK;
+    return p;
+  }
+  if (tiled_k(s)) {            // one kernel reads the tiled layout: one workgroup per head
+    if (!wants_shared(s) && decode_lds_bytes(s->S_max, s->d_h) <= lds_max) p.plan = kPlanFused;
     return p;
   }
   if (wants_shared(s)) {
@@ -300,7 +306,7 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
     ap.K = a.K; ap.Kt = one_k ? nullptr : a.Kt; ap.V = a.V; ap.v_mean = const_cast<float*>(a.v_mean); ap.seq_lens = const_cast<int32_t*>(a.seq_lens);
     ap.v_mean_out = a.v_mean_next; ap.seq_lens_out = a.seq_lens_next;
     ap.k_new = a.k_new; ap.v_new = a.v_new; ap.n_new_per_seq = nullptr; ap.err = a.err;
-    ap.B = a.B; ap.H_kv = a.H_kv; ap.S_max = a.S_max; ap.d_h = a.d_h; ap.n_new = 1;
+    ap.B = a.B; ap.H_kv = a.H_kv; ap.S_max = a.S_max; ap.d_h = a.d_h; ap.n_new = 1; ap.tiled = tiled_k(shape) ? 1 : 0;
     hipError_t e = launch_append(ap, shape->dtype, s);
     if (e != hipSuccess) return e;
     d.v_mean = a.v_mean_next; d.seq_lens = a.seq_lens_next;
@@ -428,7 +434,7 @@ int sparq_kv_append(const sparq_shape* shape, const sparq_cache* cache, const vo
   a.K = cache->K; a.Kt = single_k(shape) ? nullptr : cache->Kt; a.V = cache->V; a.v_mean = cache->v_mean; a.seq_lens = cache->seq_lens;
   a.v_mean_out = cache->v_mean; a.seq_lens_out = cache->seq_lens;
   a.k_new = k_new; a.v_new = v_new; a.n_new_per_seq = n_new_per_seq; a.err = static_cast<int32_t*>(workspace);
-  a.B = shape->B; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h; a.n_new = n_new;
+  a.B = shape->B; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h; a.n_new = n_new; a.tiled = tiled_k(shape) ? 1 : 0;
   return launch_append(a, shape->dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
@@ -514,6 +520,7 @@ int dense_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
   if (!q || !out || !aligned16(q) || !aligned16(out)) return SPARQ_EINVAL;
   rc = check_workspace(shape, workspace, workspace_bytes);
   if (rc != SPARQ_OK) return rc;
+  if (tiled_k(shape)) return SPARQ_EUNSUPPORTED;   // the comparison kernel reads key rows
   DenseArgs a;
   a.K = cache->K; a.V = cache->V; a.seq_lens = cache->seq_lens; a.q = q; a.out = out;
   a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kControlBytes);

@@ -177,10 +177,13 @@ __device__ __forceinline__ Window make_window(int local_window, int S, int kq) {
 // a two-deep software pipeline: a batch of 8 loads is always in flight behind the one being accumulated,
 // also across chunk boundaries.  fp32 FMA in ascending channel order.  finish(c, acc) is called with the
 // 8 sums of chunk c.  No barrier.
+// Addressing: chunk c of channel row j lies at Kt_head + j * row_bytes + c * chunk_bytes.  The S-contiguous
+// key copy has row_bytes = 2 S_max and chunk_bytes = 16; the tiled single-copy layout (tiles of 8 positions,
+// channel-major inside a tile) has row_bytes = 16 and chunk_bytes = 16 d_h.
 template <class T, int STRIDE = NT, class Finish>
 __device__ __forceinline__ void stream_channel_rows(const char* Kt_head, size_t row_bytes, const int* chan,
                                                     const float* qs, int r, int chunk_begin, int chunk_end,
-                                                    int tid, Finish&& finish) {
+                                                    int tid, Finish&& finish, uint32_t chunk_bytes = 16u) {
   const int n_batches = (r + 7) >> 3;
   const int n_chunks = chunk_end - chunk_begin;
   const int my_chunks = n_chunks > tid ? (n_chunks - tid + STRIDE - 1) / STRIDE : 0;
@@ -188,7 +191,7 @@ __device__ __forceinline__ void stream_channel_rows(const char* Kt_head, size_t 
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   int ic = 0, ib = 0, cc = 0, cb = 0;   // issue and consume cursors: (own chunk number, batch)
   auto issue_next = [&](uint4 (&v)[8]) {
-    const uint32_t voff = (uint32_t)(chunk_begin + tid + ic * STRIDE) * 16u;
+    const uint32_t voff = (uint32_t)(chunk_begin + tid + ic * STRIDE) * chunk_bytes;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       const int ch = __builtin_amdgcn_readfirstlane(chan[ib * 8 + t]);   // uniform: scalar row base
@@ -264,10 +267,9 @@ __device__ __forceinline__ float tail_row_dot(const TailRow& t, const float* qs,
   return wave_sum(part);
 }
 
-// Columns S-8 .. S-1 of Kt for channel j of one KV head, S a multiple of 8: rows S-8 .. S-2 of K (cached
-// by earlier calls) and `newest`, the code of the row being appended.  One 16-byte store.
-__device__ __forceinline__ void flush_key_columns(uint16_t* Kt_head, const uint16_t* K_head, int S_max, int d_h,
-                                                  int S, int j, uint16_t newest) {
+// Positions S-8 .. S-1 of channel j of one KV head, S a multiple of 8, as 16 bytes: rows S-8 .. S-2 of
+// K_head (cached by earlier calls) and `newest`, the code of the row being appended.
+__device__ __forceinline__ uint4 gather_key_columns(const uint16_t* K_head, int d_h, int S, int j, uint16_t newest) {
   uint32_t w[4];
 #pragma unroll
   for (int e = 0; e < 8; e += 2) {
@@ -275,7 +277,12 @@ __device__ __forceinline__ void flush_key_columns(uint16_t* Kt_head, const uint1
     const uint32_t hi = e + 1 < 7 ? K_head[(size_t)(S - 8 + e + 1) * d_h + j] : (uint32_t)newest;
     w[e >> 1] = lo | (hi << 16);
   }
-  *reinterpret_cast<uint4*>(Kt_head + (size_t)j * S_max + (S - 8)) = make_uint4(w[0], w[1], w[2], w[3]);
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+// ... written as columns S-8 .. S-1 of Kt: one 16-byte store
+__device__ __forceinline__ void flush_key_columns(uint16_t* Kt_head, const uint16_t* K_head, int S_max, int d_h,
+                                                  int S, int j, uint16_t newest) {
+  *reinterpret_cast<uint4*>(Kt_head + (size_t)j * S_max + (S - 8)) = gather_key_columns(K_head, d_h, S, j, newest);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -460,10 +467,15 @@ struct RowGeometry {
 // slice `sub`).  LPR lanes share a row, K and V rows are issued together, groups of UNR loads run
 // through a two-deep software pipeline.  q8 = the lane's 8 query components times log2(e)/sqrt(d_h).
 // Accumulates into (m_run, l_run, acc).  No barrier.
-template <class T, int DH>
+// TILED: the keys come from the tiled single-copy layout instead: K_head is the head's first tile (tiles of
+// 8 positions, channel-major inside a tile: element (position p, channel j) at ((p / 8) d_h + j) 8 + p % 8),
+// so a lane's 8 channels of one position are eight 2-byte loads 16 bytes apart; positions from tiled_below on
+// (the up to 7 newest, not yet in a tile) are rows of K_stage (row p - tiled_below, already offset by `sub`).
+template <class T, int DH, bool TILED = false>
 __device__ __forceinline__ void attend_rows(const char* K_head, const char* V_head, const int* list, int n_begin,
                                             int n_end, const float (&q8)[8], int lane, int wave, float& m_run,
-                                            float& l_run, float (&acc)[8]) {
+                                            float& l_run, float (&acc)[8], const char* K_stage = nullptr,
+                                            int tiled_below = 0) {
   using G = RowGeometry<DH>;
   const int slot = wave * G::RPW + lane / G::LPR;
   const int n_groups = (n_end - n_begin + G::GROUP - 1) / G::GROUP;
@@ -471,8 +483,18 @@ __device__ __forceinline__ void attend_rows(const char* K_head, const char* V_he
 #pragma unroll
     for (int t = 0; t < G::UNR; ++t) {
       const int n = n_begin + g * G::GROUP + t * G::RPI + slot;
-      const uint32_t off = (uint32_t)list[n < n_end ? n : n_end - 1] * (uint32_t)(DH * 2);   // < S_max * 512 bytes
-      kr[t] = load16(K_head + off);
+      const int p = list[n < n_end ? n : n_end - 1];
+      const uint32_t off = (uint32_t)p * (uint32_t)(DH * 2);   // < S_max * 512 bytes
+      if (!TILED) {
+        kr[t] = load16(K_head + off);
+      } else if (p >= tiled_below) {
+        kr[t] = load16(K_stage + (uint32_t)(p - tiled_below) * (uint32_t)(DH * 2));
+      } else {
+        const uint16_t* tp = reinterpret_cast<const uint16_t*>(K_head) +
+                             ((size_t)(p >> 3) * DH + (lane % G::LPR) * 8) * 8 + (p & 7);
+        const uint32_t c0 = tp[0], c1 = tp[8], c2 = tp[16], c3 = tp[24], c4 = tp[32], c5 = tp[40], c6 = tp[48], c7 = tp[56];
+        kr[t] = make_uint4(c0 | (c1 << 16), c2 | (c3 << 16), c4 | (c5 << 16), c6 | (c7 << 16));
+      }
       vr[t] = load16(V_head + off);
     }
   };

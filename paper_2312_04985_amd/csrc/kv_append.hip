@@ -140,6 +140,160 @@ __global__ __launch_bounds__(BT) void append_rows(const AppendArgs a) {
   }
 }
 
+// ---- the tiled single-copy key layout: tiles of 8 positions, channel-major inside a tile ----
+// K element (position p, channel j) of a KV head lies at ((p / 8) d_h + j) 8 + p % 8; the rows of the
+// positions 8 floor(S / 8) .. S - 1, which do not fill a tile yet, wait in a buffer of 8 rows per KV head
+// (AppendArgs::Kt) and move into their tile, as one contiguous block, when the eighth arrives.
+
+// transpose 8 rows x 8 channels of 16-bit codes (rows[e] = the 16 bytes of row e) and store the 8 channels'
+// position runs: 128 contiguous bytes at `dst`
+__device__ __forceinline__ void store_tile_piece(uint16_t* dst, const uint4 (&rows)[8]) {
+  uint32_t w[8][4];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { w[e][0] = rows[e].x; w[e][1] = rows[e].y; w[e][2] = rows[e].z; w[e][3] = rows[e].w; }
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {            // channel c of the piece: positions 0..7
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+      const uint32_t lo = (c & 1) ? (w[e][c >> 1] >> 16) : (w[e][c >> 1] & 0xffffu);
+      const uint32_t hi = (c & 1) ? (w[e + 1][c >> 1] >> 16) : (w[e + 1][c >> 1] & 0xffffu);
+      o[e >> 1] = lo | (hi << 16);
+    }
+    reinterpret_cast<uint4*>(dst)[c] = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
+// one row per sequence: one workgroup per sequence, a thread moves one 16-byte chunk (8 channels) of one KV head
+template <class T>
+__global__ __launch_bounds__(512) void append_one_row_tiled(const AppendArgs a) {
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int S = a.seq_lens[b];
+  int n = a.n_new_per_seq ? a.n_new_per_seq[b] : 1;
+  n = n < 0 ? 0 : (n > 1 ? 1 : n);
+  const bool in_place = a.v_mean_out == a.v_mean;
+  const bool full = S < 0 || S + 1 > a.S_max;
+  if (n == 0 || full) {      // nothing appended: the state is carried over unchanged
+    if (full && n != 0 && tid == 0) atomicOr(a.err, 1);
+    if (!in_place) {
+      for (int i = tid; i < a.H_kv * a.d_h; i += 512) {
+        const size_t e = (size_t)b * a.H_kv * a.d_h + i;
+        a.v_mean_out[e] = a.v_mean[e];
+      }
+      if (tid == 0) a.seq_lens_out[b] = S;
+    }
+    return;
+  }
+  const int cpr = a.d_h / 8;
+  const int n_chunks = a.H_kv * cpr;
+  const float inv = 1.0f / (float)(S + 1);
+  const int slot = S & 7;
+  for (int c = tid; c < n_chunks; c += 512) {
+    const int hk = c / cpr, j0 = (c - hk * cpr) * 8;
+    const size_t head = (size_t)b * a.H_kv + hk;
+    const uint4 kc = load16(reinterpret_cast<const uint16_t*>(a.k_new) + head * a.d_h + j0);
+    const uint4 vc = load16(reinterpret_cast<const uint16_t*>(a.v_new) + head * a.d_h + j0);
+    uint16_t* stage = reinterpret_cast<uint16_t*>(a.Kt) + head * (size_t)(8 * a.d_h);
+    *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(a.V) + (head * a.S_max + S) * a.d_h + j0) = vc;
+    if (slot != 7) {
+      *reinterpret_cast<uint4*>(stage + slot * a.d_h + j0) = kc;
+    } else {               // the eighth row: this thread's 8 channels of the finished tile
+      uint4 rows[8];
+#pragma unroll
+      for (int e = 0; e < 7; ++e) rows[e] = load16(stage + e * a.d_h + j0);
+      rows[7] = kc;
+      store_tile_piece(reinterpret_cast<uint16_t*>(a.K) + (head * a.S_max + (size_t)(S - 7)) * a.d_h + (size_t)j0 * 8, rows);
+    }
+    const float* vm = a.v_mean + head * a.d_h + j0;
+    float* vo = a.v_mean_out + head * a.d_h + j0;
+    float4 m0 = *reinterpret_cast<const float4*>(vm), m1 = *reinterpret_cast<const float4*>(vm + 4);
+    if (S == 0) m0 = m1 = make_float4(0.f, 0.f, 0.f, 0.f);
+    float f[8];
+    unpack8<T>(vc, f);
+    m0.x += (f[0] - m0.x) * inv; m0.y += (f[1] - m0.y) * inv; m0.z += (f[2] - m0.z) * inv; m0.w += (f[3] - m0.w) * inv;
+    m1.x += (f[4] - m1.x) * inv; m1.y += (f[5] - m1.y) * inv; m1.z += (f[6] - m1.z) * inv; m1.w += (f[7] - m1.w) * inv;
+    *reinterpret_cast<float4*>(vo) = m0;
+    *reinterpret_cast<float4*>(vo + 4) = m1;
+  }
+  __syncthreads();
+  if (tid == 0) a.seq_lens_out[b] = S + 1;
+}
+
+// many rows per sequence: one workgroup per (sequence, KV head); the positions go tile by tile: thread (row e,
+// chunk sub) of a tile brings its 16 bytes (from the buffer of waiting rows for positions cached before this
+// call, else from k_new) into LDS, and the threads of the first row write the tile's 128-byte pieces; the rows
+// of an unfinished last tile go (back) into the buffer.  V rows and the mean as in append_rows.
+template <class T, int DH>
+__global__ __launch_bounds__(BT) void append_rows_tiled(const AppendArgs a) {
+  constexpr int CPR = DH / 8;            // 16-byte chunks per row
+  constexpr int TPP = BT / (8 * CPR);    // tiles per pass (BT = 256: 4, 2 or 1)
+  constexpr int RPP = BT / CPR;          // value rows per pass
+  __shared__ __align__(16) uint16_t tile[TPP * 8 * DH];
+  __shared__ double colsum[RPP][DH];
+  const int tid = threadIdx.x;
+  const size_t head = blockIdx.x;
+  const int b = (int)(head / a.H_kv);
+  const int S = a.seq_lens[b];
+  int n = a.n_new_per_seq ? a.n_new_per_seq[b] : a.n_new;
+  n = n < 0 ? 0 : (n > a.n_new ? a.n_new : n);
+  if (n == 0) return;
+  if (S < 0 || S + n > a.S_max) {
+    if (tid == 0) atomicOr(a.err, 1);
+    return;
+  }
+  const uint16_t* ksrc = reinterpret_cast<const uint16_t*>(a.k_new) + head * a.n_new * DH;
+  const uint16_t* vsrc = reinterpret_cast<const uint16_t*>(a.v_new) + head * a.n_new * DH;
+  uint16_t* Kdst = reinterpret_cast<uint16_t*>(a.K) + head * a.S_max * (size_t)DH;
+  uint16_t* stage = reinterpret_cast<uint16_t*>(a.Kt) + head * (size_t)(8 * DH);
+  uint16_t* Vdst = reinterpret_cast<uint16_t*>(a.V) + (head * a.S_max + S) * DH;
+  // keys, tile by tile
+  const int sub = tid % CPR, e = (tid / CPR) & 7, tl = tid / (8 * CPR);
+  const int g_first = S >> 3, g_last = (S + n - 1) >> 3;
+  for (int g0 = g_first; g0 <= g_last; g0 += TPP) {
+    const int g = g0 + tl, p = g * 8 + e;                 // this thread's tile and position
+    const bool have = g <= g_last && p < S + n;
+    uint4 kc = make_uint4(0u, 0u, 0u, 0u);
+    if (have) kc = p < S ? load16(stage + e * DH + sub * 8) : load16(ksrc + (size_t)(p - S) * DH + sub * 8);
+    *reinterpret_cast<uint4*>(tile + (tl * 8 + e) * DH + sub * 8) = kc;
+    __syncthreads();
+    if (g <= g_last) {
+      if (g * 8 + 8 <= S + n) {                           // a finished tile
+        if (e == 0) {
+          uint4 rows[8];
+#pragma unroll
+          for (int r = 0; r < 8; ++r) rows[r] = *reinterpret_cast<const uint4*>(tile + (tl * 8 + r) * DH + sub * 8);
+          store_tile_piece(Kdst + ((size_t)g * DH + sub * 8) * 8, rows);
+        }
+      } else if (have && p >= S) {                        // a new row that waits for its tile
+        *reinterpret_cast<uint4*>(stage + e * DH + sub * 8) = kc;
+      }
+    }
+    __syncthreads();
+  }
+  // values and their column sums
+  const int prow = tid / CPR;
+  double sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int rr = prow; rr < n; rr += RPP) {
+    const size_t off = (size_t)rr * DH + sub * 8;
+    const uint4 vc = load16(vsrc + off);
+    *reinterpret_cast<uint4*>(Vdst + off) = vc;
+    float f[8];
+    unpack8<T>(vc, f);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) sum[c] += (double)f[c];
+  }
+#pragma unroll
+  for (int c = 0; c < 8; ++c) colsum[prow][sub * 8 + c] = sum[c];
+  __syncthreads();
+  if (tid < DH) {
+    double tot = 0.0;
+    for (int p = 0; p < RPP; ++p) tot += colsum[p][tid];
+    float* vm = a.v_mean + head * DH + tid;
+    const double before = S > 0 ? (double)S * (double)*vm : 0.0;
+    *vm = (float)((before + tot) / (double)(S + n));
+  }
+}
+
 __global__ void bump_seq_lens(const AppendArgs a) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= a.B) return;
@@ -217,9 +371,12 @@ template <class T>
 hipError_t launch_rows(const AppendArgs& a, hipStream_t s) {
   const dim3 grid(a.B * a.H_kv);
   switch (a.d_h) {
-    case 64:  hipLaunchKernelGGL((append_rows<T, 64>), grid, dim3(BT), 0, s, a); break;
-    case 128: hipLaunchKernelGGL((append_rows<T, 128>), grid, dim3(BT), 0, s, a); break;
-    case 256: hipLaunchKernelGGL((append_rows<T, 256>), grid, dim3(BT), 0, s, a); break;
+    case 64:  if (a.tiled) hipLaunchKernelGGL((append_rows_tiled<T, 64>), grid, dim3(BT), 0, s, a);
+              else hipLaunchKernelGGL((append_rows<T, 64>), grid, dim3(BT), 0, s, a); break;
+    case 128: if (a.tiled) hipLaunchKernelGGL((append_rows_tiled<T, 128>), grid, dim3(BT), 0, s, a);
+              else hipLaunchKernelGGL((append_rows<T, 128>), grid, dim3(BT), 0, s, a); break;
+    case 256: if (a.tiled) hipLaunchKernelGGL((append_rows_tiled<T, 256>), grid, dim3(BT), 0, s, a);
+              else hipLaunchKernelGGL((append_rows<T, 256>), grid, dim3(BT), 0, s, a); break;
     default: return hipErrorInvalidValue;
   }
   hipError_t e = hipGetLastError();
@@ -232,7 +389,10 @@ hipError_t launch_rows(const AppendArgs& a, hipStream_t s) {
 
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t s) {
   if (a.n_new == 1) {
-    if (dtype == 1) hipLaunchKernelGGL(append_one_row<BF16>, dim3(a.B), dim3(512), 0, s, a);
+    if (a.tiled) {
+      if (dtype == 1) hipLaunchKernelGGL(append_one_row_tiled<BF16>, dim3(a.B), dim3(512), 0, s, a);
+      else hipLaunchKernelGGL(append_one_row_tiled<F16>, dim3(a.B), dim3(512), 0, s, a);
+    } else if (dtype == 1) hipLaunchKernelGGL(append_one_row<BF16>, dim3(a.B), dim3(512), 0, s, a);
     else hipLaunchKernelGGL(append_one_row<F16>, dim3(a.B), dim3(512), 0, s, a);
     return hipGetLastError();
   }

@@ -31,6 +31,7 @@ struct AppendArgs {
   float* v_mean_out; int32_t* seq_lens_out;   // where the new means / lengths go (== v_mean / seq_lens: in place)
   const void* k_new; const void* v_new; const int32_t* n_new_per_seq; int32_t* err;
   int32_t B, H_kv, S_max, d_h, n_new;
+  int32_t tiled;   // the tiled single-copy key layout: K holds tiles of 8 positions, Kt the rows of the newest < 8
 };
 
 struct DenseArgs {

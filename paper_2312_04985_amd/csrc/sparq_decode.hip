@@ -47,7 +47,11 @@ __device__ __forceinline__ Lds carve(uint32_t* base, int S_max) {
 // takes that row from the inputs; the workgroup of the first query head of a KV group also writes
 // it into K, V and Kt and stores the updated mean; lengths and means go to the *_next buffers, so no
 // workgroup can observe another one's update of the state it reads.
-template <class T, int DH, bool APPEND>
+// TILED = true reads the single-copy tiled key layout (flag bit 6): a.K holds tiles of 8 positions, channel-major
+// inside a tile, a.Kt the up to 7 newest rows of every KV head (8 rows of d_h each) that do not fill a tile yet.
+// Step 1b then strides through the tiles (16 bytes per position chunk and channel), Step 2b collects a row's
+// components from its tile, and the append writes a row of the small buffer, or a whole tile with the eighth row.
+template <class T, int DH, bool APPEND, bool TILED>
 __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) {
   extern __shared__ __align__(16) uint32_t smem[];
   const Lds L = carve<DH>(smem, a.S_max);
@@ -133,7 +137,9 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   // (in the one-launch step Kt is up to date for the length before this call: the group of 8 that the new
   // row may complete is written during this launch, so up to 8 positions come from rows)
   const int S_fl = ((APPEND && appended) ? S - 1 : S) & ~7, n_tail = S - S_fl, r8 = (a.r + 7) & ~7;
-  const uint16_t* K_rows = reinterpret_cast<const uint16_t*>(a.K) + kv_head * a.S_max * (size_t)DH;
+  // rows of K by position (two-copy layout), or the rows of the newest positions S_fl .. (tiled layout)
+  const uint16_t* K_rows = TILED ? reinterpret_cast<const uint16_t*>(a.Kt) + kv_head * (size_t)(8 * DH) - (size_t)S_fl * DH
+                                 : reinterpret_cast<const uint16_t*>(a.K) + kv_head * a.S_max * (size_t)DH;
   TailRow tail;
   const bool tail_is_new = APPEND && appended && wave == n_tail - 1;
   if (wave < n_tail) {
@@ -142,8 +148,9 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   }
 
   // ---------------- stage 1 ----------------
-  const size_t row_bytes = (size_t)a.S_max * 2;
-  const char* Kt_head = reinterpret_cast<const char*>(a.Kt) + kv_head * DH * row_bytes;
+  const size_t row_bytes = TILED ? 16 : (size_t)a.S_max * 2;
+  const char* Kt_head = TILED ? reinterpret_cast<const char*>(a.K) + kv_head * a.S_max * (size_t)(DH * 2)
+                              : reinterpret_cast<const char*>(a.Kt) + kv_head * DH * row_bytes;
   float tmax = -INFINITY;
   auto finish = [&](int c, const float (&acc)[8]) {
     uint32_t kx[8];
@@ -157,7 +164,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
     dst[0] = make_uint4(kx[0], kx[1], kx[2], kx[3]);
     dst[1] = make_uint4(kx[4], kx[5], kx[6], kx[7]);
   };
-  stream_channel_rows<T>(Kt_head, row_bytes, L.qry.chan, L.qry.qs, a.r, 0, S_fl >> 3, tid, finish);
+  stream_channel_rows<T>(Kt_head, row_bytes, L.qry.chan, L.qry.qs, a.r, 0, S_fl >> 3, tid, finish, TILED ? DH * 16u : 16u);
   if (wave < n_tail) {
     const float dot = tail_row_dot<T>(tail, L.qry.qs, r8, lane);
     tmax = fmaxf(tmax, dot);
@@ -201,7 +208,11 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   const bool new_selected = APPEND && appended && list[kq - 1] == S - 1;
   float m_run = -INFINITY, l_run = 0.0f;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  attend_rows<T, DH>(K_head, V_head, list, 0, new_selected ? kq - 1 : kq, q8, lane, wave, m_run, l_run, acc);
+  if (TILED)
+    attend_rows<T, DH, true>(Kt_head, V_head, list, 0, new_selected ? kq - 1 : kq, q8, lane, wave, m_run, l_run, acc,
+                             reinterpret_cast<const char*>(K_rows + (size_t)S_fl * DH) + sub * 16, S_fl);
+  else
+    attend_rows<T, DH>(K_head, V_head, list, 0, new_selected ? kq - 1 : kq, q8, lane, wave, m_run, l_run, acc);
   if (APPEND && new_selected) attend_row_from_codes<T, DH>(L.knew, L.vnew, q8, lane, wave, m_run, l_run, acc);
   store_wave_partial<DH>(m_run, l_run, acc, L.part, lane, wave);
   __syncthreads();
@@ -223,32 +234,40 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
     a.v_mean_next[kv_head * DH + tid] = __uint_as_float(L.qry.mag[tid]);
     if (appended) {
       const uint16_t kc = L.knew[tid];
-      reinterpret_cast<uint16_t*>(a.K)[(kv_head * a.S_max + (S - 1)) * DH + tid] = kc;
       reinterpret_cast<uint16_t*>(a.V)[(kv_head * a.S_max + (S - 1)) * DH + tid] = L.vnew[tid];
-      // a step that completes a group of 8 positions copies it to Kt (one 16-byte store per channel row)
-      if ((S & 7) == 0)
-        flush_key_columns(reinterpret_cast<uint16_t*>(a.Kt) + kv_head * DH * (size_t)a.S_max, K_rows, a.S_max, DH, S, tid, kc);
+      if (!TILED) {
+        reinterpret_cast<uint16_t*>(a.K)[(kv_head * a.S_max + (S - 1)) * DH + tid] = kc;
+        // a step that completes a group of 8 positions copies it to Kt (one 16-byte store per channel row)
+        if ((S & 7) == 0)
+          flush_key_columns(reinterpret_cast<uint16_t*>(a.Kt) + kv_head * DH * (size_t)a.S_max, K_rows, a.S_max, DH, S, tid, kc);
+      } else if ((S & 7) != 0) {
+        const_cast<uint16_t*>(K_rows)[(size_t)(S - 1) * DH + tid] = kc;        // row (S - 1) mod 8 of the small buffer
+      } else {
+        // the eighth row completes a tile: channel tid's 8 positions are 16 contiguous bytes of it
+        const uint4 cols = gather_key_columns(K_rows, DH, S, tid, kc);
+        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(a.K) + (kv_head * a.S_max + (size_t)(S - 8)) * DH + (size_t)tid * 8) = cols;
+      }
     }
   }
 }
 
-template <class T, int DH, bool APPEND>
+template <class T, int DH, bool APPEND, bool TILED>
 hipError_t launch_one(const DecodeArgs& a, hipStream_t s) {
   const size_t lds = decode_lds_bytes(a.S_max, DH);
-  auto kern = sparq_decode_fused<T, DH, APPEND>;
-  hipError_t e = allow_lds<sparq_decode_fused<T, DH, APPEND>>(lds);
+  auto kern = sparq_decode_fused<T, DH, APPEND, TILED>;
+  hipError_t e = allow_lds<sparq_decode_fused<T, DH, APPEND, TILED>>(lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(a.B * a.H), dim3(NT), lds, s, a);
   return hipGetLastError();
 }
 
-template <bool APPEND>
+template <bool APPEND, bool TILED>
 hipError_t launch_any(const DecodeArgs& a, int dtype, hipStream_t s) {
   const bool bf = dtype == 1;
   switch (a.d_h) {
-    case 64:  return bf ? launch_one<BF16, 64, APPEND>(a, s) : launch_one<F16, 64, APPEND>(a, s);
-    case 128: return bf ? launch_one<BF16, 128, APPEND>(a, s) : launch_one<F16, 128, APPEND>(a, s);
-    case 256: return bf ? launch_one<BF16, 256, APPEND>(a, s) : launch_one<F16, 256, APPEND>(a, s);
+    case 64:  return bf ? launch_one<BF16, 64, APPEND, TILED>(a, s) : launch_one<F16, 64, APPEND, TILED>(a, s);
+    case 128: return bf ? launch_one<BF16, 128, APPEND, TILED>(a, s) : launch_one<F16, 128, APPEND, TILED>(a, s);
+    case 256: return bf ? launch_one<BF16, 256, APPEND, TILED>(a, s) : launch_one<F16, 256, APPEND, TILED>(a, s);
     default:  return hipErrorInvalidValue;
   }
 }
@@ -260,7 +279,8 @@ size_t decode_lds_bytes(int S_max, int d_h) {
 }
 
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s) {
-  return a.k_new ? launch_any<true>(a, dtype, s) : launch_any<false>(a, dtype, s);
+  if (a.flags & 64u) return a.k_new ? launch_any<true, true>(a, dtype, s) : launch_any<false, true>(a, dtype, s);
+  return a.k_new ? launch_any<true, false>(a, dtype, s) : launch_any<false, false>(a, dtype, s);
 }
 
 }  // namespace sparq

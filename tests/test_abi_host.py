@@ -43,7 +43,7 @@ def test_workspace_bytes_and_shape_validation():
     assert B.sparq_workspace_bytes(shape(S_max=32768, B=1, H=32, H_kv=8)) > need
     for bad, code in [(dict(S_max=100), B.SPARQ_EINVAL), (dict(H=5), B.SPARQ_EINVAL), (dict(r=0), B.SPARQ_EINVAL),
                       (dict(r=129), B.SPARQ_EINVAL), (dict(k=0), B.SPARQ_EINVAL), (dict(dtype=2), B.SPARQ_EINVAL),
-                      (dict(flags=64), B.SPARQ_EINVAL), (dict(flags=8 | 16), B.SPARQ_EINVAL), (dict(local_window=-1), B.SPARQ_EINVAL),
+                      (dict(flags=128), B.SPARQ_EINVAL), (dict(flags=32 | 64), B.SPARQ_EINVAL), (dict(flags=8 | 16), B.SPARQ_EINVAL), (dict(local_window=-1), B.SPARQ_EINVAL),
                       (dict(B=0), B.SPARQ_EINVAL), (dict(d_h=80, r=16), B.SPARQ_EUNSUPPORTED)]:
         with pytest.raises(B.SparqError) as e:
             B.sparq_workspace_bytes(shape(**bad))
@@ -87,6 +87,8 @@ def test_shapes_without_a_kernel_are_refused_before_any_launch():
         dict(S_max=65536, flags=B.SPARQ_FLAG_SINGLE_K, H=2, H_kv=2),
         dict(H=8, H_kv=1, flags=B.SPARQ_FLAG_GQA_SHARED),            # groups of 8 query heads
         dict(flags=B.SPARQ_FLAG_GQA_SHARED | B.SPARQ_FLAG_SINGLE_K),
+        dict(flags=B.SPARQ_FLAG_GQA_SHARED | B.SPARQ_FLAG_TILED_K),
+        dict(S_max=65536, flags=B.SPARQ_FLAG_TILED_K, H=2, H_kv=2),     # the tiled layout is read by the one-workgroup kernel only
     ]
     for kw in refused:
         assert call_decode(shape(**kw), good) == B.SPARQ_EUNSUPPORTED, kw

@@ -30,7 +30,7 @@ def say(*a):
 def run(w, *, n_q=1, q_scale=1.0, tie_channels=0, flags=0, local_window=0, **build_kw):
     say(f"[case] {w.name} B={w.B} H={w.H}/{w.H_kv} d_h={w.d_h} S={w.S} r={w.r} k={w.k} {w.dtype} "
         f"ragged={w.ragged} q_scale={q_scale} flags={flags} l={local_window} {build_kw}")
-    b = Hn.build_cache(w, flags=flags & B.SPARQ_FLAG_SINGLE_K, **build_kw)     # a single-copy cache gets no Kt at all
+    b = Hn.build_cache(w, flags=flags & (B.SPARQ_FLAG_SINGLE_K | B.SPARQ_FLAG_TILED_K), **build_kw)     # the cache is built in its layout
     q = W.draw_queries(w, b.K_src, b.seq_lens, n=n_q, q_scale=q_scale, tie_channels=tie_channels)
     stats = None
     for i in range(n_q):
@@ -443,6 +443,58 @@ def test_single_copy_key_cache(name, kw, extra):
     st = run(w, flags=B.SPARQ_FLAG_SINGLE_K, q_scale=0.02, v_offset=True, seq_lens=seq, single_appends=3, **extra)
     # whatever the band of the fp32 rounding bound leaves uncompared must stay a sliver of the positions
     assert st["uncompared_fp32_bound"] <= 0.001 * float(seq.sum()) * w.H
+
+
+@pytest.mark.parametrize("name,kw,extra", [
+    ("tk_mha", dict(B=3, H=4, H_kv=4, d_h=128, S=3000, r=32, k=256, dtype="f16"), {}),
+    ("tk_gqa_bf16", dict(B=2, H=8, H_kv=2, d_h=128, S=2100, r=16, k=128, dtype="bf16"), {}),
+    ("tk_d64", dict(B=3, H=2, H_kv=2, d_h=64, S=777, r=8, k=64, dtype="f16"), {}),
+    ("tk_d256_long", dict(B=1, H=2, H_kv=2, d_h=256, S=20000, r=64, k=1024, dtype="bf16"), {}),
+    ("tk_window", dict(B=2, H=4, H_kv=4, d_h=128, S=1000, r=16, k=64, dtype="f16"), dict(local_window=16)),
+    ("tk_short", dict(B=4, H=2, H_kv=2, d_h=128, S=70, r=16, k=100, dtype="f16"), {}),
+])
+def test_tiled_single_copy_key_cache(name, kw, extra):
+    """SPARQ_FLAG_TILED_K: one key copy in tiles of 8 positions that serves both steps.  The cache is built in
+    that layout through the library (bulk append to ragged lengths, then one-row appends, so tiles are finished
+    by both paths and every sequence ends at another place inside a tile)."""
+    w = W.Workload(name, seed=71, **kw)
+    seq = torch.tensor([max(1, w.S - 41 * i) for i in range(w.B)], dtype=torch.int32)
+    st = run(w, flags=B.SPARQ_FLAG_TILED_K, q_scale=0.02, v_offset=True, seq_lens=seq, single_appends=11, **extra)
+    assert st["uncompared_fp32_bound"] <= 0.001 * float(seq.sum()) * w.H
+
+
+def test_tiled_step_equals_append_then_decode_and_refusals():
+    w = W.Workload("tk_step", 3, 4, 2, 128, 530, 16, 64, "f16", seed=72)
+    seq = torch.tensor([530, 523, 9], dtype=torch.int32)
+    b = Hn.build_cache(w, flags=B.SPARQ_FLAG_TILED_K, v_offset=True, seq_lens=seq, single_appends=3, S_max=576)
+    twin = Hn.build_cache(w, flags=B.SPARQ_FLAG_TILED_K, v_offset=True, seq_lens=seq, single_appends=3, S_max=576)
+    kn, vn = W.draw_kv(W.scaled(w, seed=901), "cuda", n_rows=20, v_offset=True)
+    for t in range(20):                               # crosses tile boundaries of every sequence
+        cur = seq + t + 1
+        q = W.draw_queries(w, torch.cat([b.K_src, kn[:, :, :t + 1]], dim=2), cur, q_scale=0.02, stream=t)[0]
+        k1, v1 = kn[:, :, t].contiguous(), vn[:, :, t].contiguous()
+        b.cache.with_params(w.r, w.k, B.SPARQ_FLAG_TILED_K); twin.cache.with_params(w.r, w.k, B.SPARQ_FLAG_TILED_K)
+        out = b.cache.step(k1, v1, q)
+        twin.cache.append(k1, v1)
+        ref = twin.cache.decode(q)
+        torch.cuda.synchronize()
+        assert torch.equal(b.cache.key_rows(), twin.cache.key_rows()) and torch.equal(b.cache.V, twin.cache.V)
+        assert (b.cache.v_mean - twin.cache.v_mean).abs().max().item() <= 1e-6
+        assert (out.float() - ref.float()).abs().max().item() <= 1e-3
+    # every sequence's rows: its first S_b source rows, then the 20 appended ones
+    rows = b.cache.key_rows()
+    for i in range(w.B):
+        s0 = int(seq[i])
+        assert torch.equal(rows[i, :, :s0], b.K_src[i, :, :s0]) and torch.equal(rows[i, :, s0:s0 + 20], kn[i])
+    assert b.cache.error_flags() == 0
+    # what the tiled layout is not combined with
+    q = W.draw_queries(w, b.K_src, seq)[0]
+    with pytest.raises(B.SparqError) as e:
+        b.cache.dense(q)
+    assert e.value.status == B.SPARQ_EUNSUPPORTED
+    with pytest.raises(B.SparqError) as e:
+        b.cache.with_params(w.r, w.k, B.SPARQ_FLAG_TILED_K | B.SPARQ_FLAG_GQA_SHARED).decode(q)
+    assert e.value.status == B.SPARQ_EUNSUPPORTED
 
 
 def test_single_copy_step_and_refusals():
