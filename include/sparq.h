@@ -161,10 +161,12 @@ int sparq_kv_append(const sparq_shape* shape, const sparq_cache* cache, const vo
  *   Step 3  alpha = sum_{i in i2} s_hat_i;  y = alpha y3 + (1 - alpha) v_mean
  * Arithmetic is fp32 on the 16-bit inputs; `out` is rounded to nearest-even.
  * Sizes: every plan keeps 4 bytes per position (or per candidate) of its unit of work in LDS.  One
- * workgroup per head serves S_max up to about 35 000; longer caches are selected in two levels (spans of
- * 8192 positions, at most 64 of them, ceil(S_max / 8192) * min(k, 8192) candidates <= about 36 000: e.g.
- * S_max = 524 288 at k = 512), also under SPARQ_FLAG_GQA_SHARED.  SPARQ_FLAG_SINGLE_K stops at about 35 000.
- * Anything else returns SPARQ_EUNSUPPORTED before a launch.
+ * workgroup per head serves S_max up to about 35 000.  Batches of at most 128 (sequence, head) units with
+ * S_max >= 8192 are spread over spans of up to 8192 positions (at most 64 spans: S_max <= 524 288, any k).
+ * Larger batches with longer caches are selected in two levels (spans of 8192 positions, at most 64 of
+ * them, ceil(S_max / 8192) * min(k, 8192) candidates <= about 36 000: e.g. S_max = 524 288 at k = 512), also
+ * under SPARQ_FLAG_GQA_SHARED.  SPARQ_FLAG_SINGLE_K and SPARQ_FLAG_TILED_K stop at about 35 000.
+ * Anything else returns SPARQ_EUNSUPPORTED before a launch.  sparq_decode_plan names the kernels of a shape.
  *   q          device [B, H, d_h]
  *   k_per_seq  device [B] or NULL; k_per_seq[b] in 1..shape.k replaces shape.k for sequence b
  *              (shape.k is the maximum that buffers are sized for: values outside are clamped)

@@ -54,37 +54,6 @@ void dense_plan(const sparq_shape* s, int* n_split, int* rows_per_split) {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// The split-sequence plan serves batches with few (sequence, head) units and long caches: the
-// positions of every unit are divided over n_split workgroups (about 512 workgroups in all, slices
-// of at least 1024 positions).  Everything else runs one workgroup per unit.
-bool split_plan(const sparq_shape* s, int* n_split) {
-  const int64_t units = (int64_t)s->B * s->H;
-  if (units > kSplitMaxUnits || s->S_max < 8192) return false;
-  int64_t n = 512 / units;
-  if (n > kMaxSplit) n = kMaxSplit;
-  if (n > s->S_max / 1024) n = s->S_max / 1024;
-  *n_split = (int)n;
-  return n >= 2;
-}
-
-// workspace: [0, kControlBytes) control block (error word, arrival counters), then either the
-// dense_decode partials or the arrays of the split-sequence / long-sequence plan (never live together)
-struct SplitLayout { size_t tmax, tau, alpha, keys, list, part, end; };
-
-SplitLayout split_layout(const sparq_shape* s, int n_split) {
-  const size_t units = (size_t)s->B * s->H;
-  SplitLayout l;
-  size_t off = kControlBytes;
-  l.tmax = off; off = align256(off + units * n_split * sizeof(float));
-  l.tau = off; off = align256(off + units * sizeof(float));
-  l.alpha = off; off = align256(off + units * sizeof(float));
-  l.keys = off; off = align256(off + units * s->S_max * sizeof(uint32_t));
-  l.list = off; off = align256(off + units * s->S_max * sizeof(int32_t));
-  l.part = off; off = align256(off + units * n_split * (s->d_h + 2) * sizeof(float));
-  l.end = off;
-  return l;
-}
-
 // LDS a workgroup may use: the device's, or gfx950's 160 KiB where no device can be asked (sizing
 // queries on a machine without a GPU)
 int max_lds_bytes() {
@@ -109,14 +78,12 @@ bool tiled_k(const sparq_shape* shape) { return (shape->flags & SPARQ_FLAG_TILED
 
 // Which kernels serve a shape.  Every plan keeps one 4-byte key per position (or per candidate) of its
 // unit of work in LDS; that decides what fits.
-enum Plan { kPlanNone, kPlanFused, kPlanSplit, kPlanLong, kPlanShared, kPlanSharedSplit, kPlanSingleK, kPlanBucket };
+enum Plan { kPlanNone, kPlanFused, kPlanLong, kPlanShared, kPlanSharedSplit, kPlanSingleK, kPlanBucket };
 struct PlanInfo { Plan plan; int n_split, n_span, span_len, cand_cap, n1, span1; };
 
 // The two-level plan: spans of `span` positions select their own top-k, one workgroup per unit merges at
-// most n_span * min(k, span) candidates.  It serves what no single workgroup can hold (S_max beyond the
-// LDS), and batches with few units and long caches when a span is longer than k, i.e. when the merge sees
-// fewer keys than a select over the whole sequence would (measured against the split-sequence plan:
-// 58 vs 62 us at B = 1, 32 heads, S = 32768, k = 2048; 50 vs 63 us at k = 512; 39 vs 43 us at S = 16384).
+// most n_span * min(k, span) candidates.  It serves what no single workgroup can hold (S_max beyond the LDS)
+// for batches with more units than the digit-bucket plan takes.
 bool two_level_plan(const sparq_shape* s, int span, size_t lds_max, PlanInfo* p) {
   const int64_t n_span = ((int64_t)s->S_max + span - 1) / span;
   if (n_span > kMaxSpans) return false;
@@ -203,11 +170,6 @@ PlanInfo choose_plan(const sparq_shape* s) {
     return p;
   }
   if ((int64_t)s->B * s->H <= kSplitMaxUnits && s->S_max >= 8192 && bucket_plan(s, lds_max, &p)) { p.plan = kPlanBucket; return p; }
-  if ((int64_t)s->B * s->H <= kSplitMaxUnits && s->S_max >= 16384) {
-    const int span = s->S_max >= 32768 ? kLongSpan : kLongSpan / 2;
-    if (s->k < span && two_level_plan(s, span, lds_max, &p)) { p.plan = kPlanLong; return p; }
-  }
-  if (split_plan(s, &p.n_split) && split_select_lds_bytes(s->S_max) <= lds_max) { p.plan = kPlanSplit; return p; }
   if (decode_lds_bytes(s->S_max, s->d_h) <= lds_max) { p.plan = kPlanFused; return p; }
   if (two_level_plan(s, kLongSpan, lds_max, &p)) p.plan = kPlanLong;
   return p;
@@ -279,7 +241,6 @@ size_t workspace_need(const sparq_shape* s) {
   size_t need = (size_t)kControlBytes + (size_t)s->B * s->H * n_split * (s->d_h + 2) * sizeof(float);
   const PlanInfo p = choose_plan(s);
   size_t e = 0;
-  if (p.plan == kPlanSplit) e = split_layout(s, p.n_split).end;
   if (p.plan == kPlanLong) e = long_layout(s, p).end;
   if (p.plan == kPlanBucket) e = bucket_layout(s, p).end;
   if (p.plan == kPlanShared) e = (size_t)kControlBytes + (size_t)s->B * s->H * s->S_max * sizeof(float);
@@ -366,17 +327,7 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
     la.part_ws = reinterpret_cast<float*>(w + l.part);
     return launch_decode_long(la, shape->dtype, s);
   }
-  const SplitLayout l = split_layout(shape, p.n_split);
-  SplitArgs sa;
-  sa.d = d;
-  sa.n_split = p.n_split;
-  sa.tmax_ws = reinterpret_cast<float*>(w + l.tmax);
-  sa.tau_ws = reinterpret_cast<float*>(w + l.tau);
-  sa.alpha_ws = reinterpret_cast<float*>(w + l.alpha);
-  sa.keys_ws = reinterpret_cast<uint32_t*>(w + l.keys);
-  sa.list_ws = reinterpret_cast<int32_t*>(w + l.list);
-  sa.part_ws = reinterpret_cast<float*>(w + l.part);
-  return launch_decode_split(sa, shape->dtype, s);
+  return hipErrorInvalidValue;
 }
 
 bool decode_supported(const sparq_shape* shape) { return choose_plan(shape).plan != kPlanNone; }
@@ -553,7 +504,6 @@ const char* sparq_decode_plan(const sparq_shape* shape) {
   if (check_shape(shape) != SPARQ_OK) return "invalid shape";
   switch (choose_plan(shape).plan) {
     case kPlanFused: return "sparq_decode_fused (one workgroup per head, one launch)";
-    case kPlanSplit: return "split_scores + split_select + split_gather + split_combine (split-sequence plan)";
     case kPlanLong: return "long_scores + long_merge + split_gather + split_combine (two-level selection plan)";
     case kPlanBucket: return "bk_scores + bk_select_gather + bk_combine (digit-bucket plan)";
     case kPlanShared: return "sparq_decode_shared (grouped-query rule, one workgroup per KV head)";

@@ -1,8 +1,9 @@
 // The stages of the SparQ decode step (Section 4, Steps 1-3) as workgroup-level device functions.
 // Every decode plan is a different distribution of these stages over workgroups: one workgroup per
-// (sequence, head) (sparq_decode.hip), split-sequence (sparq_decode_split.hip), two-level selection
+// (sequence, head) (sparq_decode.hip), digit buckets over spans (sparq_decode_bucket.hip), two-level selection
 // (sparq_decode_long.hip), the grouped-query rule (sparq_decode_shared.hip), the single-copy key cache
-// (sparq_decode_single_k.hip); the append kernels use the column flush.
+// (sparq_decode_single_k.hip); sparq_decode_split.hip holds the gather and merge launches that the
+// multi-launch plans share; the append kernels use the column flush.
 // Unless noted, functions are called by all kDecodeThreads threads of a workgroup (they contain barriers).
 #pragma once
 #include "common.h"

@@ -11,7 +11,7 @@ constexpr int kRadixBins = 2048;        // 11-bit digits: passes of 11, 11 and 1
 constexpr int kWorkspaceHeader = 256;   // bytes; word 0 is the error word
 constexpr int kControlBytes = 65536;    // control block at the start of the workspace, zeroed by sparq_workspace_init
 constexpr int kMaxSplit = 16;           // most workgroups one (sequence, head) is split over
-constexpr int kSplitMaxUnits = 128;     // the split-sequence plan serves at most this many (sequence, head) units
+constexpr int kSplitMaxUnits = 128;     // the digit-bucket plan (few units, long caches) serves at most this many (sequence, head) units
 constexpr int kProbeBlocks = 256 * 8;   // workgroups (of 256 threads) of the bandwidth probes
 
 struct DecodeArgs {
@@ -41,7 +41,6 @@ struct DenseArgs {
   int32_t B, H, H_kv, S_max, d_h, n_split, rows_per_split;
 };
 
-// split-sequence plan (few heads, long sequences): workspace arrays and the split count
 // two-level plan: spans of span_len positions (a multiple of 64, at most kLongSpan), at most kMaxSpans per sequence
 constexpr int kLongSpan = 8192;
 constexpr int kMaxSpans = 64;
@@ -82,13 +81,11 @@ struct GsArgs {
   float* part_ws;          // [B * H][n_split][d_h + 2] attention partials
 };
 
+// the gather and merge launches shared by the multi-launch plans
 struct SplitArgs {
   DecodeArgs d;
-  int32_t n_split;       // workgroups per (sequence, head) in both launches
-  float* tmax_ws;        // [B * H][n_split] largest logit numerator of each slice
-  float* tau_ws;         // [B * H]
+  int32_t n_split;       // gather workgroups per (sequence, head)
   float* alpha_ws;       // [B * H]
-  uint32_t* keys_ws;     // [B * H][S_max] integer keys of the approximate logits
   int32_t* list_ws;      // [B * H][S_max] selected positions, ascending
   float* part_ws;        // [B * H][n_split][d_h + 2] attention partials
 };
@@ -112,7 +109,6 @@ struct BucketArgs {
 
 // LDS bytes the fused decode kernel needs for a cache of S_max rows and head dimension d_h
 size_t decode_lds_bytes(int S_max, int d_h);
-size_t split_select_lds_bytes(int S_max);
 size_t decode_shared_lds_bytes(int S_max, int d_h, int g);   // 0: no grouped-query kernel for this shape
 
 hipError_t launch_decode(const DecodeArgs& a, int dtype, hipStream_t s);
@@ -125,7 +121,7 @@ size_t bk_scores_lds_bytes(int span_len, int d_h);
 size_t bk_select_lds_bytes(int span_len, int d_h, int n_span, int cand_cap);
 int bk_fine_len();
 hipError_t launch_decode_bucket(const BucketArgs& a, int dtype, hipStream_t s);
-// the last two launches of the split-sequence plan (gather over slices of list_ws, merge): uses d, n_split,
+// the gather launch and the merge (gather over slices of list_ws, merge): uses d, n_split,
 // alpha_ws, list_ws, part_ws of `a`
 hipError_t launch_split_gather(const SplitArgs& a, int dtype, hipStream_t s);
 // the last launch alone: uses d, n_split, alpha_ws, part_ws
@@ -135,7 +131,6 @@ size_t gs_merge_lds_bytes(int n2, int cand_cap);
 hipError_t launch_decode_shared_split(const GsArgs& a, int dtype, hipStream_t s);
 // z_ws: [B * H][S_max] fp32 scratch for the logit numerators
 hipError_t launch_decode_shared(const DecodeArgs& a, float* z_ws, int dtype, hipStream_t s);
-hipError_t launch_decode_split(const SplitArgs& a, int dtype, hipStream_t s);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t s);
 hipError_t launch_dense(const DenseArgs& a, int dtype, hipStream_t s);
 hipError_t launch_copy_probe(void* dst, const void* src, size_t n_bytes, hipStream_t s);

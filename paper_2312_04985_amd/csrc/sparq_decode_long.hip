@@ -1,5 +1,6 @@
-// SparQ decode for sequences too long for one workgroup's LDS (one 4-byte key per cached position does
-// not fit beyond ~35 000 positions).  The top-k of a sequence is contained in the union of the top-k of
+// SparQ decode for many (sequence, head) units with sequences too long for one workgroup's LDS (one 4-byte
+// key per cached position does not fit beyond ~35 000 positions; few units with long caches go through the
+// digit-bucket plan instead).  The top-k of a sequence is contained in the union of the top-k of
 // its parts (a position beaten by fewer than k others overall is beaten by fewer than k in its own part,
 // ties to the lower position in both), so the selection of Step 2 is made in two levels:
 //   long_scores    (units x n_span workgroups) Step 1 on a span of span_len positions, keys in LDS; the
@@ -7,8 +8,7 @@
 //                  position-ascending, with the span's largest logit and its softmax denominator
 //   long_merge     (one workgroup per unit) the candidates of all spans into LDS (at most n_span x k),
 //                  the same radix select and ordered compaction over them, alpha, the position list
-//   split_gather / split_combine   exact attention over slices of the list, merge and blend (the last two
-//                  launches of the split-sequence plan)
+//   split_gather / split_combine   exact attention over slices of the list, merge and blend
 // The local window is part of both levels: its positions are the last ones of the sequence, every span
 // hands on those it holds, and they are the last candidates of the merge.
 #include "decode_stages.h"
@@ -258,7 +258,7 @@ hipError_t launch_long(const LongArgs& a, int dtype, hipStream_t s) {
   if ((e = hipGetLastError()) != hipSuccess) return e;
   SplitArgs g;
   g.d = a.d; g.n_split = a.n_split;
-  g.tmax_ws = nullptr; g.tau_ws = a.tau_ws; g.alpha_ws = a.alpha_ws; g.keys_ws = nullptr;
+  g.alpha_ws = a.alpha_ws;
   g.list_ws = a.list_ws; g.part_ws = a.part_ws;
   return launch_split_gather(g, dtype, s);
 }

@@ -494,7 +494,7 @@ hipError_t launch_gs(const GsArgs& a, int dtype, hipStream_t s) {
   if ((e = hipGetLastError()) != hipSuccess) return e;
   SplitArgs c;
   c.d = a.d; c.n_split = a.n_split;
-  c.tmax_ws = nullptr; c.tau_ws = nullptr; c.alpha_ws = a.alpha_ws; c.keys_ws = nullptr; c.list_ws = nullptr;
+  c.alpha_ws = a.alpha_ws; c.list_ws = nullptr;
   c.part_ws = a.part_ws;
   return launch_split_combine(c, dtype, s);
 }

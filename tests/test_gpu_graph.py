@@ -1,7 +1,7 @@
 """HIP graph capture of the decode step (GPU).  The library allocates nothing, never synchronises and
 clears its control words with a kernel, so a step can be recorded into a graph; what is recorded here is
 two consecutive steps (the ping-pong of the length / mean buffers returns to its start after two), for
-the one-launch kernel and for the multi-launch split-sequence plan.  Every replay is checked against a
+the one-launch kernel and for the multi-launch digit-bucket plan.  Every replay is checked against a
 twin cache stepped eagerly, with eager work and synchronisations between the replays."""
 import pytest
 import torch

@@ -357,10 +357,10 @@ def test_decode_step_on_a_full_sequence():
     assert torch.equal(b.cache.Kt[1, :, :, :32], b.cache.K[1, :, :32].transpose(-1, -2))
 
 
-# ------------------------------------------------------------------ split-sequence plan (few heads, long cache)
+# ------------------------------------------------------------------ digit-bucket plan (few heads, long cache)
 
 def test_split_plan_ragged_short_and_empty_sequences():
-    """S_max >= 8192 with few heads selects the split-sequence kernels; sequences much shorter than the
+    """S_max >= 8192 with few heads selects the digit-bucket kernels; sequences much shorter than the
     slices (empty slices), k >= S, an empty sequence and every d_h go through them too."""
     for d_h, dtype, r in ((128, "f16", 16), (256, "bf16", 64), (64, "f16", 8)):
         w = W.Workload("split_ragged", 4, 4, 2, d_h, 9000, r, 200, dtype, seed=40 + d_h)
@@ -393,7 +393,7 @@ def test_fixed_temperatures(flag):
     wg = W.Workload("tau_modes_gqa", 2, 8, 2, 128, 1100, 16, 96, "bf16", seed=61)
     run(wg, flags=flag, q_scale=0.02, v_offset=True)                                  # independent heads
     run(wg, flags=flag | B.SPARQ_FLAG_GQA_SHARED, q_scale=0.02, v_offset=True)        # the paper's group rule
-    ws = W.Workload("tau_modes_split", 1, 4, 4, 128, 9000, 32, 300, "f16", seed=62)   # split-sequence plan
+    ws = W.Workload("tau_modes_split", 1, 4, 4, 128, 9000, 32, 300, "f16", seed=62)   # digit-bucket plan
     run(ws, flags=flag, q_scale=0.01, v_offset=True)
 
 
