@@ -50,6 +50,10 @@ __device__ __forceinline__ float key_to_float(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
+// 2^x as the hardware's one instruction.  exp2f() wraps it in range scaling so that results below 2^-126 come
+// out as denormals; a softmax weight that small adds nothing to a sum whose largest term is 1.
+__device__ __forceinline__ float exp2_weight(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // ---- wave64 primitives (DPP: no LDS traffic, a few cycles each) ----
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v) {

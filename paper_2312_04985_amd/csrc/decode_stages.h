@@ -418,22 +418,41 @@ __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t
     const uint32_t gt_before = run_gt + (ex & 0xffffu);
     uint32_t eq_before = run_eq + (ex >> 16);
     uint32_t o = gt_before + (eq_before < (uint32_t)need ? eq_before : (uint32_t)need);
+    // the taken keys of this chunk: everything above the threshold and the first equal keys while they are needed
+    uint32_t take_bits = gt_bits;
+    if (eq_bits) {
+      uint32_t eb = eq_bits;
+      for (int room = need - (int)eq_before; eb && room > 0; --room) {
+        const uint32_t low = eb & (0u - eb);
+        take_bits |= low; eb ^= low;
+      }
+    }
+    if (WITH_ALPHA) {   // softmax weights of all 8 keys, without branches
+      const int n_valid = c < n_chunks ? S - c * 8 : 0;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const bool valid = (c * 8 + e) < S && c < n_chunks;
-      if (valid) {
-        const float w = WITH_ALPHA ? exp2f((key_to_float(kx[e]) - dmax) * esc) : 0.0f;
+      for (int e = 0; e < 8; ++e) {
+        float w = exp2_weight((key_to_float(kx[e]) - dmax) * esc);
+        w = e < n_valid ? w : 0.0f;
         zsum += w;
-        bool take = (gt_bits >> e) & 1u;
-        if ((eq_bits >> e) & 1u) { take = eq_before < (uint32_t)need; ++eq_before; }
-        if (take) {
-          asum += w;
+        asum += ((take_bits >> e) & 1u) ? w : 0.0f;
+      }
+    }
+    if (key_out == nullptr) {   // few keys are taken: visit only those
+      for (uint32_t tb = take_bits; tb; tb &= tb - 1) {
+        const int pos = pos_base + c * 8 + (__ffs(tb) - 1);
+        list[o] = (uint32_t)pos;
+        if (idx_out && (int)o < idx_stride) idx_out[o] = pos;
+        ++o;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if ((take_bits >> e) & 1u) {
           list[o] = (uint32_t)(pos_base + c * 8 + e);
-          if (key_out) key_out[o] = kx[e];
+          key_out[o] = kx[e];
           if (idx_out && (int)o < idx_stride) idx_out[o] = pos_base + c * 8 + e;
           ++o;
         }
-      }
     }
     run_gt += total & 0xffffu;
     run_eq += total >> 16;
@@ -511,7 +530,7 @@ __device__ __forceinline__ void attend_rows(const char* K_head, const char* V_he
       dot = lanes_sum<G::LPR>(dot);
       if (n < n_end) {
         const float m_new = fmaxf(m_run, dot);
-        const float sc = exp2f(m_run - m_new), pr = exp2f(dot - m_new);
+        const float sc = exp2_weight(m_run - m_new), pr = exp2_weight(dot - m_new);
         unpack8<T>(vr[t], f);
         l_run = l_run * sc + pr;
 #pragma unroll
@@ -555,7 +574,7 @@ __device__ __forceinline__ void attend_row_from_codes(const uint16_t* krow, cons
   dot = lanes_sum<G::LPR>(dot);
   if (wave == 0 && lane < G::LPR) {
     const float m_new = fmaxf(m_run, dot);
-    const float sc = exp2f(m_run - m_new), pr = exp2f(dot - m_new);
+    const float sc = exp2_weight(m_run - m_new), pr = exp2_weight(dot - m_new);
     unpack8<T>(*reinterpret_cast<const uint4*>(vrow + sub * 8), f);
     l_run = l_run * sc + pr;
 #pragma unroll

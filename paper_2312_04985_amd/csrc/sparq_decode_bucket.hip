@@ -13,9 +13,8 @@
 //               the best are: they are read by every workgroup of the unit and ranked exactly by
 //               (key descending, position ascending) with radix passes over the remaining 21 key bits and,
 //               only among identical keys, over the position.  Each workgroup then writes its own span's
-//               selected positions, ascending (into idx_out at its place in the unit's list), its share of alpha's
-//               numerator
-//               numerator, gathers its own span's selected rows of K and V (Step 2b) and leaves one
+//               selected positions, ascending (into idx_out at its place in the unit's list), its share of
+//               alpha's numerator, gathers its own span's selected rows of K and V (Step 2b) and leaves one
 //               attention partial per span
 //   bk_combine  (one workgroup per unit) merges the spans' partials, alpha, blend, store
 // Every workgroup attends over the selected rows of its own span: the gather is balanced when the selected
