@@ -31,7 +31,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 CLOCK_WARMUP_STEPS = 300       # untimed steps before the W warm-up steps: the first ~10 ms after idle run at lower clocks
 HEADLINE = "c4_large_batch"
-OTHERS = ["c1_single_head", "c2_llama2_7b", "c3_llama3_8b_gqa", "c5_gemma_7b_ragged"]
+OTHERS = ["c1_single_head", "c2_llama2_7b", "c3_llama3_8b_gqa", "c5_gemma_7b_ragged", "paper_table2"]
 OUT_TOL = 2e-3                 # max abs error of the 16-bit output against the oracle's fp64 y (the tests' bar)
 
 
@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-others", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--stage-clocks", action="store_true",
+                    help="profiling run on libsparq_clocks.so (python -m paper_2312_04985_amd.build --stage-clocks): prints the "
+                         "per-stage time stamps of the step kernel's workgroups instead of the benchmark line")
     ap.add_argument("--layout", choices=["two_copies", "single_k", "tiled_k"], default="two_copies",
                     help="key cache layout: K twice (default), once row-major (SPARQ_FLAG_SINGLE_K), once in tiles (SPARQ_FLAG_TILED_K)")
     return ap.parse_args()
@@ -85,6 +88,41 @@ def output_violations(got, y, dtype_code):
     else:
         bad = (got < round_to_format(y - OUT_TOL, dtype_code)) | (got > round_to_format(y + OUT_TOL, dtype_code))
     return int(bad.sum()), float(diff.max())
+
+
+STAGES = ["stage 0: lengths, query, top-r channels, tau", "Step 1 stream (first wave's share)", "wait: all waves' scores in LDS",
+          "Step 2 radix select", "Step 2 compaction, alpha", "Step 2 gather + attention (first wave's share)",
+          "wait: all waves' partials in LDS", "merge, blend, output and append stores"]
+
+
+def stage_clock_summary(caches, B):
+    """Per-stage durations from the time stamps a profiling build leaves in every cache copy's workspace (the last
+    step launched on that copy)."""
+    import numpy as np
+    off, n_wg, n_st = B.sparq_stage_clocks(caches[0].shape)
+    dur, total, span, starts, drain = [], [], [], [], []
+    for c in caches:
+        t = c.workspace[off:off + n_wg * n_st * 8].view(torch_int64()).cpu().numpy().reshape(n_wg, n_st).astype(np.float64) * 0.01
+        t0 = t[:, 0].min()
+        dur.append(np.diff(t, axis=1)); total.append(t[:, -1] - t[:, 0]); span.append(t[:, -1].max() - t0)
+        starts.append(np.sort(t[:, 0] - t0))
+        ends = np.sort(t[:, -1] - t0)
+        drain.append(ends[-1] - np.median(ends[-min(n_wg, 512):]))
+    dur = np.concatenate(dur); total = np.concatenate(total)
+    q = lambda x: {"median": round(float(np.median(x)), 2), "p10": round(float(np.percentile(x, 10)), 2),
+                   "p90": round(float(np.percentile(x, 90)), 2), "mean": round(float(np.mean(x)), 2)}
+    st = np.stack(starts)
+    return {"unit": "us", "workgroups_per_launch": n_wg, "launches": len(caches),
+            "stages": {STAGES[i]: q(dur[:, i]) for i in range(len(STAGES))},
+            "workgroup_total": q(total), "launch_span_first_start_to_last_end": q(np.array(span)),
+            "workgroups_started_within_2us": int(np.median((st < 2.0).sum(axis=1))),
+            "start_of_workgroup_number": {str(n): round(float(np.median(st[:, n])), 2) for n in (0, 511, 512, 1023, 1024, 1535, 1536, n_wg - 1) if n < n_wg},
+            "last_end_minus_median_end_of_last_512": q(np.array(drain))}
+
+
+def torch_int64():
+    import torch
+    return torch.int64
 
 
 def measure(name, K, Wm, args, full):
@@ -212,6 +250,14 @@ def measure(name, K, Wm, args, full):
     if flags:
         raise RuntimeError(f"device error word set during the timed region: {flags}")
 
+    if args.stage_clocks:
+        rec = {"workload": name, "step_us_instrumented_build": round(ms_per_step * 1e3, 2),
+               "plan": B.sparq_decode_plan(caches[0].shape), "stage_clocks": stage_clock_summary(caches, B)}
+        del caches, table, cs, K_src, V_src
+        gc.collect()
+        torch.cuda.empty_cache()
+        return rec
+
     # ---- average duration of the step's launches over the same K steps, HIP events on their stream;
     # K back-to-back steps, launch gaps included; then once more with an event after every step ----
     restore()
@@ -257,7 +303,7 @@ def measure(name, K, Wm, args, full):
                           "how": "one HIP event after every step of a separate pass of K steps"},
         "two_launch_step_ms": round(two_call_ms, 5), "decode_launch_ms": round(dec_avg_ms, 5),
         "decode_launch_GBps": round(dec_bytes0 / dec_avg_ms / 1e6, 1), "append_launch_ms": round(append_ms, 5),
-        "roofline": {"kernel": plan + (" with the append built in (sparq_decode_step)" if plan.startswith("sparq_decode_fused") else
+        "roofline": {"kernel": plan + (" with the append built in (sparq_decode_step)" if plan.startswith(("sparq_decode_fused", "bk_scores")) else
                                        "; sparq_decode_step runs append_one_row first"),
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic_from_profile(name),
@@ -354,6 +400,14 @@ def main():
 
     name = args.workload or HEADLINE
     K, Wm = args.steps, args.warmup
+    if args.stage_clocks:
+        from paper_2312_04985_amd import binding, build
+        if not os.path.exists(build.LIB_CLOCKS):
+            print("bench.py --stage-clocks needs libsparq_clocks.so: python -m paper_2312_04985_amd.build --stage-clocks", file=sys.stderr)
+            sys.exit(1)
+        binding.LIB_PATH = build.LIB_CLOCKS
+        print(json.dumps(measure(name, K, Wm, args, full=False)))
+        return
     main_rec = measure(name, K, Wm, args, full=True)
 
     rec = {

@@ -201,9 +201,11 @@ int sparq_decode_noalloc(const sparq_shape* shape, const sparq_cache* cache, con
                          int32_t idx_stride, int32_t* chan_out, int32_t* error_word, void* hip_stream);
 
 /*
- * The whole decode step in one launch: exactly sparq_kv_append with n_new = 1 followed by
+ * The whole decode step in one call: exactly sparq_kv_append with n_new = 1 followed by
  * sparq_decode (Section 4: the step writes k and v, updates the mean value vector and attends
- * over the cache including the new token), except that the small state is not updated in place:
+ * over the cache including the new token).  One launch where one workgroup serves a head; the
+ * three launches of the few-heads-long-cache plan with the append in the last one; for the other
+ * plans the append kernel followed by the decode launches.  The small state is not updated in place:
  * the new lengths and means are written to seq_lens_next [B] and v_mean_next [B, H_kv, d_h]
  * (device, must not alias cache->seq_lens / cache->v_mean, which are only read) and the caller
  * swaps the two pairs of buffers between steps.  K and V receive row S_b in place, Kt as in
@@ -242,6 +244,16 @@ int sparq_read_probe(const void* src, size_t n_bytes, void* sink, size_t sink_by
 /* Which kernels sparq_decode / sparq_decode_step launch for this shape (a static string naming the plan
  * and its launches; "unsupported" where sparq_decode would return SPARQ_EUNSUPPORTED).  Host only. */
 const char* sparq_decode_plan(const sparq_shape* shape);
+
+/* Profiling builds only (the library compiled with -DSPARQ_STAGE_CLOCKS; the default build returns
+ * SPARQ_EUNSUPPORTED): for shapes served by one workgroup per head, every sparq_decode / sparq_decode_step
+ * launch also leaves *stamps_per_workgroup 64-bit time stamps per workgroup (10 ns ticks of the device's
+ * constant 100 MHz counter; workgroups in launch order) at workspace + *offset_bytes: start, Step 1 channels
+ * selected, the first wave's share of the Step 1 stream done, all approximate scores in LDS, Step 2 threshold
+ * found, position list compacted, the first wave's rows attended, all partial results in LDS, end.
+ * sparq_workspace_bytes of such a build includes the room.  Host only. */
+int sparq_stage_clocks(const sparq_shape* shape, size_t* offset_bytes, int32_t* n_workgroups,
+                       int32_t* stamps_per_workgroup);
 
 const char* sparq_status_string(int status);
 

@@ -23,7 +23,7 @@ SPARQ_OK, SPARQ_EINVAL, SPARQ_EUNSUPPORTED, SPARQ_EWORKSPACE, SPARQ_ELAUNCH, SPA
 
 EXPORTS = ["sparq_workspace_bytes", "sparq_workspace_init", "sparq_kv_append", "sparq_decode", "sparq_decode_noalloc", "sparq_decode_step",
            "dense_decode", "sparq_async_error", "sparq_copy_probe", "sparq_read_probe", "sparq_decode_plan",
-           "sparq_status_string"]
+           "sparq_stage_clocks", "sparq_status_string"]
 
 
 class SparqShape(ctypes.Structure):
@@ -70,6 +70,7 @@ def load() -> ctypes.CDLL:
     L.sparq_read_probe.argtypes = [vp, sz, vp, sz, vp]
     L.sparq_status_string.argtypes = [ctypes.c_int]
     L.sparq_decode_plan.argtypes = [shp]
+    L.sparq_stage_clocks.argtypes = [shp, ctypes.POINTER(sz), ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.sparq_decode_plan.restype = ctypes.c_char_p
     L.sparq_status_string.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -81,6 +82,13 @@ def load() -> ctypes.CDLL:
 
 def sparq_decode_plan(shape: SparqShape) -> str:
     return load().sparq_decode_plan(ctypes.byref(shape)).decode()
+
+
+def sparq_stage_clocks(shape: SparqShape):
+    """(offset_bytes, n_workgroups, stamps_per_workgroup) of the time stamps a profiling build leaves in the workspace."""
+    off, n, m = ctypes.c_size_t(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    _check("sparq_stage_clocks", load().sparq_stage_clocks(ctypes.byref(shape), ctypes.byref(off), ctypes.byref(n), ctypes.byref(m)))
+    return off.value, n.value, m.value
 
 
 def status_string(status: int) -> str:

@@ -245,6 +245,9 @@ size_t workspace_need(const sparq_shape* s) {
   if (p.plan == kPlanBucket) e = bucket_layout(s, p).end;
   if (p.plan == kPlanShared) e = (size_t)kControlBytes + (size_t)s->B * s->H * s->S_max * sizeof(float);
   if (p.plan == kPlanSharedSplit) e = gs_layout(s, p).end;
+#ifdef SPARQ_STAGE_CLOCKS
+  if (p.plan == kPlanFused) e = (size_t)kControlBytes + (size_t)s->B * s->H * kStageStamps * sizeof(unsigned long long);
+#endif
   return e > need ? e : need;
 }
 
@@ -257,12 +260,19 @@ int check_workspace(const sparq_shape* s, const void* ws, size_t bytes) {
 hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* workspace, hipStream_t s) {
   const PlanInfo p = choose_plan(shape);
   if (p.plan == kPlanNone) return hipErrorInvalidValue;
+#ifdef SPARQ_STAGE_CLOCKS
+  if (p.plan == kPlanFused) {
+    DecodeArgs c = a;
+    c.clocks = reinterpret_cast<unsigned long long*>(static_cast<char*>(workspace) + kControlBytes);
+    return launch_decode(c, shape->dtype, s);
+  }
+#endif
   if (p.plan == kPlanFused) return launch_decode(a, shape->dtype, s);
   const bool one_k = p.plan == kPlanSingleK;
   DecodeArgs d = a;
-  if (a.k_new) {
-    // only the one-workgroup-per-head kernel has the append built in: append into the *_next state
-    // with the append kernel, then decode from that state
+  if (a.k_new && p.plan != kPlanBucket) {
+    // the one-workgroup-per-head kernel and the digit-bucket plan have the append built in; the other plans
+    // append into the *_next state with the append kernel, then decode from that state
     AppendArgs ap;
     ap.K = a.K; ap.Kt = one_k ? nullptr : a.Kt; ap.V = a.V; ap.v_mean = const_cast<float*>(a.v_mean); ap.seq_lens = const_cast<int32_t*>(a.seq_lens);
     ap.v_mean_out = a.v_mean_next; ap.seq_lens_out = a.seq_lens_next;
@@ -511,6 +521,19 @@ const char* sparq_decode_plan(const sparq_shape* shape) {
     case kPlanSingleK: return "sparq_decode_single_k (key cache stored once)";
     default: return "unsupported";
   }
+}
+
+int sparq_stage_clocks(const sparq_shape* shape, size_t* offset_bytes, int32_t* n_workgroups, int32_t* stamps_per_workgroup) {
+  if (!offset_bytes || !n_workgroups || !stamps_per_workgroup) return SPARQ_EINVAL;
+  const int rc = check_shape(shape);
+  if (rc != SPARQ_OK) return rc;
+#ifdef SPARQ_STAGE_CLOCKS
+  if (choose_plan(shape).plan != kPlanFused) return SPARQ_EUNSUPPORTED;
+  *offset_bytes = kControlBytes; *n_workgroups = shape->B * shape->H; *stamps_per_workgroup = kStageStamps;
+  return SPARQ_OK;
+#else
+  return SPARQ_EUNSUPPORTED;
+#endif
 }
 
 const char* sparq_status_string(int status) {

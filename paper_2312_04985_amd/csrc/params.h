@@ -24,7 +24,13 @@ struct DecodeArgs {
   int32_t B, H, H_kv, S_max, d_h, r, k, idx_stride;
   uint32_t flags;
   int32_t local_window;
+  unsigned long long* clocks = nullptr;   // [workgroups][kStageStamps] time stamps; set only by a SPARQ_STAGE_CLOCKS build
 };
+
+// Time stamps per workgroup of the one-workgroup-per-head kernel in a SPARQ_STAGE_CLOCKS build (10 ns ticks of the
+// constant 100 MHz counter): start, channels selected, own part of Step 1 done, all keys in LDS, threshold
+// found, list compacted, own rows attended, all partials in LDS, end.
+constexpr int kStageStamps = 9;
 
 struct AppendArgs {
   void* K; void* Kt; void* V; float* v_mean; int32_t* seq_lens;

@@ -14,6 +14,15 @@ namespace sparq {
 
 namespace {
 
+// A SPARQ_STAGE_CLOCKS build (a second library for profiling, never the default one) keeps nine time stamps per
+// workgroup in scalar registers and stores them when the workgroup ends; otherwise the macro is empty.
+#ifdef SPARQ_STAGE_CLOCKS
+#define SPARQ_STAMP(i) stamp[i] = wall_clock64()
+#else
+#define SPARQ_STAMP(i) do {} while (0)
+#endif
+
+
 struct Lds {
   uint32_t* keys;   // [S_max]   stage 1-2: keys; after compaction: selected positions
   SelectLds sel;
@@ -57,6 +66,10 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   const Lds L = carve<DH>(smem, a.S_max);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
+#ifdef SPARQ_STAGE_CLOCKS
+  unsigned long long stamp[kStageStamps];
+#endif
+  SPARQ_STAMP(0);
   // Workgroup -> unit.  Workgroups are dealt round-robin to the 8 XCDs and started in index order.
   // Default: every XCD gets a contiguous run of units, so the query heads of a KV group share an L2.
   // With the ragged-batch hint (and no grouped heads): workgroup i serves the sequence with the
@@ -147,6 +160,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
     else tail = tail_row_issue(K_rows + (size_t)(S_fl + wave) * DH, L.qry.chan, r8, lane);
   }
 
+  SPARQ_STAMP(1);
   // ---------------- stage 1 ----------------
   const size_t row_bytes = TILED ? 16 : (size_t)a.S_max * 2;
   const char* Kt_head = TILED ? reinterpret_cast<const char*>(a.K) + kv_head * a.S_max * (size_t)(DH * 2)
@@ -174,9 +188,11 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
       if (S_fl + wave < win.S_old) atomicAdd(&L.sel.hist[hist_slot(key >> 21)], 1u);
     }
   }
+  SPARQ_STAMP(2);
   tmax = wave_max(tmax);
   if (lane == 0) L.sel.red[wave] = tmax;
   __syncthreads();
+  SPARQ_STAMP(3);
   float dmax = L.sel.red[0];
 #pragma unroll
   for (int w = 1; w < NW; ++w) dmax = fmaxf(dmax, L.sel.red[w]);
@@ -185,8 +201,10 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   uint32_t pmask, pval;
   int need;
   radix_select(L.keys, win.S_old, win.k_old, L.sel, tid, lane, wave, pmask, pval, need);
+  SPARQ_STAMP(4);
   const float alpha = compact_selected(L.keys, L.keys, S, win.S_old, pmask, pval, need, dmax, kLog2e / tau, idx_out, a.idx_stride,
                                        L.sel, tid, lane, wave);
+  SPARQ_STAMP(5);
   if (tid == 0) {
     if (a.alpha_out) a.alpha_out[u] = alpha;
     if (idx_out && kq > a.idx_stride) atomicOr(a.err, 4);
@@ -214,8 +232,10 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   else
     attend_rows<T, DH>(K_head, V_head, list, 0, new_selected ? kq - 1 : kq, q8, lane, wave, m_run, l_run, acc);
   if (APPEND && new_selected) attend_row_from_codes<T, DH>(L.knew, L.vnew, q8, lane, wave, m_run, l_run, acc);
+  SPARQ_STAMP(6);
   store_wave_partial<DH>(m_run, l_run, acc, L.part, lane, wave);
   __syncthreads();
+  SPARQ_STAMP(7);
   if (tid < DH) {
     float m_all, l_all, y3;
     combine_partials<DH>(L.part, NW, tid, m_all, l_all, y3);
@@ -249,6 +269,11 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
       }
     }
   }
+#ifdef SPARQ_STAGE_CLOCKS
+  SPARQ_STAMP(8);
+  if (a.clocks && tid == 0)
+    for (int i = 0; i < kStageStamps; ++i) a.clocks[(size_t)blockIdx.x * kStageStamps + i] = stamp[i];
+#endif
 }
 
 template <class T, int DH, bool APPEND, bool TILED>

@@ -20,6 +20,8 @@
 // Every workgroup attends over the selected rows of its own span: the gather is balanced when the selected
 // positions are spread over the sequence, and takes as long as the busiest span when they are not.
 // The local window is part of it: its positions count as digit 2047, above every finite key.
+// Inside sparq_decode_step the three launches count the row being appended as position S_b (taken from the
+// inputs wherever it is needed) and bk_combine writes it to the cache, after every read of the earlier launches.
 #include "decode_stages.h"
 
 namespace sparq {
@@ -40,6 +42,19 @@ __device__ __forceinline__ void map_span(int U, int n_span, int& u, int& s) {
     u = bid / n_span;
     s = bid % n_span;
   }
+}
+
+// The length a launch works on.  Inside sparq_decode_step (d.k_new set) the row being appended counts as position
+// S_b although it reaches the cache only in the plan's last launch: every launch adds it the same way.
+__device__ __forceinline__ int visible_length(const DecodeArgs& d, int b, bool& appended, bool& bad, bool& full) {
+  int S = d.seq_lens[b];
+  bad = S < 0 || S > d.S_max;
+  if (bad) S = S < 0 ? 0 : d.S_max;
+  appended = false; full = false;
+  if (d.k_new) {
+    if (S + 1 <= d.S_max) { appended = true; S += 1; } else full = true;
+  }
+  return S;
 }
 
 // LDS words of bk_scores besides the three span-sized arrays
@@ -76,11 +91,9 @@ __global__ __launch_bounds__(NT, 4) void bk_scores(const BucketArgs a) {
 
   uint16_t qcode = 0;
   if (tid < DH) qcode = reinterpret_cast<const uint16_t*>(d.q)[(size_t)u * DH + tid];
-  int S = d.seq_lens[b];
-  if (S < 0 || S > d.S_max) {
-    if (tid == 0 && s == 0) atomicOr(d.err, 8);
-    S = S < 0 ? 0 : d.S_max;
-  }
+  bool appended, bad, full;
+  const int S = visible_length(d, b, appended, bad, full);
+  if (tid == 0 && s == 0 && (bad || full)) atomicOr(d.err, (bad ? 8 : 0) | (full ? 1 : 0));
   int32_t* idx_out = d.idx_out ? d.idx_out + (size_t)u * d.idx_stride : nullptr;
   if (S == 0) {   // nothing cached: span 0 writes the defined outputs, the later launches skip the unit
     if (s == 0) {
@@ -112,12 +125,17 @@ __global__ __launch_bounds__(NT, 4) void bk_scores(const BucketArgs a) {
     if (tid == 0) a.tau_ws[u] = tau;
   }
 
-  // the newest S mod 8 positions are not in Kt: the span that holds them takes them from the rows of K
-  const int S_fl = S & ~7, r8 = (d.r + 7) & ~7;
+  // the newest S mod 8 positions are not in Kt (inside a step: up to 8, Kt being up to date for the length before
+  // the call): the span that holds them takes them from the rows of K, the row being appended from the inputs
+  const int S_fl = (appended ? S - 1 : S) & ~7, r8 = (d.r + 7) & ~7;
   const int n_tail = (S_fl >= p0 && S_fl < p0 + len) ? S - S_fl : 0;
   TailRow tail;
-  if (wave < n_tail)
-    tail = tail_row_issue(reinterpret_cast<const uint16_t*>(d.K) + (kv_head * d.S_max + S_fl + wave) * (size_t)DH, chan, r8, lane);
+  if (wave < n_tail) {
+    const uint16_t* krow = appended && wave == n_tail - 1
+                               ? reinterpret_cast<const uint16_t*>(d.k_new) + kv_head * DH
+                               : reinterpret_cast<const uint16_t*>(d.K) + (kv_head * d.S_max + S_fl + wave) * (size_t)DH;
+    tail = tail_row_issue(krow, chan, r8, lane);
+  }
 
   const int end = p0 + len < S_fl ? p0 + len : S_fl;     // whole chunks of this span that are in Kt
   const size_t row_bytes = (size_t)d.S_max * 2;
@@ -280,7 +298,8 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
 
   // everything that does not depend on another load is requested at once: the lengths, the query slice of
   // Step 2, the temperature, the spans' statistics, and the coarse tables (wave w takes spans w, w + 8, ...)
-  int S = d.seq_lens[b];
+  bool appended, bad, full;
+  const int S = visible_length(d, b, appended, bad, full);
   int kb = d.k_per_seq ? d.k_per_seq[b] : d.k;
   const uint4 qraw = load16(reinterpret_cast<const uint16_t*>(d.q) + (size_t)u * DH + sub * 8);
   const float tau = a.tau_ws[u];
@@ -293,7 +312,6 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
   float tm = -INFINITY, zs = 0.0f;
   if (wave == 1 && lane < a.n_span) { tm = a.tmax_ws[slot0 + lane]; zs = a.zsum_ws[slot0 + lane]; }
 
-  S = S < 0 ? 0 : (S > d.S_max ? d.S_max : S);
   if (S == 0) return;                      // outputs written by bk_scores
   kb = kb < 1 ? 1 : (kb > d.k ? d.k : kb);
   const int kq = kb < S ? kb : S;
@@ -530,7 +548,13 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
   const char* V_head = reinterpret_cast<const char*>(d.V) + kv_head * d.S_max * (size_t)(DH * 2) + sub * 16;
   float m_run = -INFINITY, l_run = 0.0f;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  attend_rows<T, DH>(K_head, V_head, list, 0, (int)total, q8, lane, wave, m_run, l_run, acc);
+  // positions are ascending, so the row being appended (position S - 1, not in the cache yet) can only be the
+  // last entry of the last span's list: it is taken from the inputs
+  const bool new_selected = appended && total > 0 && list[total - 1] == S - 1;
+  attend_rows<T, DH>(K_head, V_head, list, 0, (int)total - (new_selected ? 1 : 0), q8, lane, wave, m_run, l_run, acc);
+  if (new_selected)
+    attend_row_from_codes<T, DH>(reinterpret_cast<const uint16_t*>(d.k_new) + kv_head * DH,
+                                 reinterpret_cast<const uint16_t*>(d.v_new) + kv_head * DH, q8, lane, wave, m_run, l_run, acc);
   store_wave_partial<DH>(m_run, l_run, acc, part, lane, wave);
   __syncthreads();
   if (tid < DH) {
@@ -549,13 +573,36 @@ __global__ __launch_bounds__(DH) void bk_combine(const BucketArgs a) {
   const int u = blockIdx.x, c = threadIdx.x;
   const int b = u / d.H, h = u - b * d.H;
   const size_t kv_head = (size_t)b * d.H_kv + h / (d.H / d.H_kv);
-  const int S = d.seq_lens[b];
+  bool appended, bad, full;
+  const int S = visible_length(d, b, appended, bad, full);
+  float vm = d.v_mean[kv_head * DH + c];
+  if (d.k_new) {
+    // the step's append, after every read of the cache by the earlier launches: the workgroup of the first query
+    // head of a KV group writes the rows, the 8 columns of Kt that the row may complete, and the new mean
+    // (the same update as sparq_kv_append's; the mean of no rows is ignored); lengths and means go to the *_next buffers
+    const uint16_t vcode = reinterpret_cast<const uint16_t*>(d.v_new)[kv_head * DH + c];
+    if (appended) {
+      if (S == 1) vm = 0.0f;
+      vm += (T::widen(vcode) - vm) * (1.0f / (float)S);
+    }
+    if (h == (h / (d.H / d.H_kv)) * (d.H / d.H_kv)) {
+      d.v_mean_next[kv_head * DH + c] = vm;
+      if (appended) {
+        const uint16_t kc = reinterpret_cast<const uint16_t*>(d.k_new)[kv_head * DH + c];
+        uint16_t* K_rows = reinterpret_cast<uint16_t*>(d.K) + kv_head * d.S_max * (size_t)DH;
+        reinterpret_cast<uint16_t*>(d.V)[(kv_head * d.S_max + (S - 1)) * DH + c] = vcode;
+        K_rows[(size_t)(S - 1) * DH + c] = kc;
+        if ((S & 7) == 0)
+          flush_key_columns(reinterpret_cast<uint16_t*>(d.Kt) + kv_head * DH * (size_t)d.S_max, K_rows, d.S_max, DH, S, c, kc);
+      }
+    }
+    if (h == 0 && c == 0) d.seq_lens_next[b] = S;
+  }
   if (S <= 0) return;                      // outputs written by bk_scores
   const float* parts = a.part_ws + (size_t)u * a.n_span * (DH + 2);
   const int ln = c & (kWave - 1);
   const float num = wave_sum(ln < a.n_span ? a.anum_ws[(size_t)u * a.n_span + ln] : 0.0f);   // fixed order
   const float zden = a.zden_ws[u];
-  const float vm = d.v_mean[kv_head * DH + c];
   float m_all = -INFINITY, l_all = 0.0f, y3 = 0.0f;
   for (int w0 = 0; w0 < a.n_span; w0 += 16) {          // sixteen partials of this channel in flight at a time
     float pm[16], pl[16], py[16];

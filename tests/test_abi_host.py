@@ -37,6 +37,24 @@ def shape(**kw):
     return B.SparqShape(*[d[f] for f, _ in B.SparqShape._fields_])
 
 
+def test_stage_clocks_exist_only_in_a_profiling_build():
+    """The default library records no time stamps and says so; a profiling build (if one has been made) describes
+    where it leaves them and asks for the room in the workspace."""
+    with pytest.raises(B.SparqError) as e:
+        B.sparq_stage_clocks(shape())
+    assert e.value.status == B.SPARQ_EUNSUPPORTED
+    from paper_2312_04985_amd import build
+    if os.path.exists(build.LIB_CLOCKS):
+        lib = ctypes.CDLL(build.LIB_CLOCKS)
+        off, n, m = ctypes.c_size_t(0), ctypes.c_int32(0), ctypes.c_int32(0)
+        sh = shape()
+        assert lib.sparq_stage_clocks(ctypes.byref(sh), ctypes.byref(off), ctypes.byref(n), ctypes.byref(m)) == 0
+        assert (off.value, n.value, m.value) == (65536, 2 * 4, 9)
+        need = ctypes.c_size_t(0)
+        assert lib.sparq_workspace_bytes(ctypes.byref(sh), ctypes.byref(need)) == 0
+        assert need.value >= 65536 + 8 * 9 * 8
+
+
 def test_workspace_bytes_and_shape_validation():
     need = B.sparq_workspace_bytes(shape())
     assert need >= 256 + 2 * 4 * (128 + 2) * 4

@@ -382,6 +382,39 @@ def test_split_plan_ragged_short_and_empty_sequences():
         say(Hn.compare_decode(sub, q[0][keep].contiguous()))
 
 
+def test_digit_bucket_plan_ties_identical_keys_and_ragged_k():
+    """The digit-bucket plan's own degenerate cases: many duplicated keys (ties inside the threshold bucket are
+    split by position), all keys identical (every key is a candidate: far more than the LDS holds, so they are
+    ranked from the workspace), a per-sequence k, and the one-call step."""
+    w = W.Workload("bucket_ties", 2, 4, 2, 128, 12000, 16, 300, "f16", seed=44, recipe="gaussian", k_div=50)
+    assert "digit-bucket" in B.sparq_decode_plan(B.make_shape(w.B, w.H, w.H_kv, 12032, w.d_h, w.r, w.k, w.dtype_code))
+    st = run(w, dup_rows=3000, n_q=2)
+    say(st)
+    seq = torch.tensor([12000, 8700], dtype=torch.int32)
+    b = Hn.build_cache(w, seq_lens=seq, S_max=12032, dup_rows=2500, v_offset=True)
+    b = Hn.Built(w, b.cache, b.K_src, b.V_src, b.seq_lens, W.k_per_seq(w, seq))
+    q = W.draw_queries(w, b.K_src, b.seq_lens, q_scale=0.02)[0]
+    say(Hn.compare_decode(b, q))
+    kn, vn = W.draw_kv(W.scaled(w, seed=45), "cuda", n_rows=1, v_offset=True)
+    out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q, b.k_per_seq.cuda())
+    torch.cuda.synchronize()
+    assert b.cache.seq_lens.cpu().tolist() == [12001, 8701] and b.cache.error_flags() == 0
+    assert torch.equal(out.view(torch.int16), b.cache.decode(q, b.k_per_seq.cuda()).view(torch.int16))
+    # all keys identical: every score ties, the k lowest positions must be selected
+    w1 = W.scaled(w, B=1, k_div=None)
+    c = Hn.build_cache(w1)
+    c.K_src[:] = c.K_src[:, :, :1]
+    c = Hn.Built(w1, DecodeCache(w1.B, w1.H, w1.H_kv, 12032, w1.d_h, w1.r, w1.k, w1.torch_dtype), c.K_src, c.V_src, c.seq_lens, None)
+    c.cache.append(c.K_src, c.V_src)
+    q = W.draw_queries(w1, c.K_src, c.seq_lens)[0]
+    out, alpha, idx, chan = c.cache.decode(q, aux=True)
+    torch.cuda.synchronize()
+    assert c.cache.error_flags() == 0
+    assert torch.equal(idx.cpu(), torch.arange(w1.k, dtype=torch.int32).expand(w1.B, w1.H, w1.k))
+    assert torch.allclose(alpha.cpu(), torch.full((w1.B, w1.H), w1.k / w1.S), atol=1e-6)
+    Hn.compare_decode(c, q)
+
+
 # ------------------------------------------------------------------ ablation switches
 
 @pytest.mark.parametrize("flag", [B.SPARQ_FLAG_TAU_SQRT_DH, B.SPARQ_FLAG_TAU_SQRT_R])
