@@ -78,7 +78,7 @@ bool tiled_k(const sparq_shape* shape) { return (shape->flags & SPARQ_FLAG_TILED
 
 // Which kernels serve a shape.  Every plan keeps one 4-byte key per position (or per candidate) of its
 // unit of work in LDS; that decides what fits.
-enum Plan { kPlanNone, kPlanFused, kPlanLong, kPlanShared, kPlanSharedSplit, kPlanSingleK, kPlanBucket };
+enum Plan { kPlanNone, kPlanFused, kPlanLong, kPlanShared, kPlanSharedSplit, kPlanSingleK, kPlanBucket, kPlanSharedBucket };
 struct PlanInfo { Plan plan; int n_split, n_span, span_len, cand_cap, n1, span1; };
 
 // The two-level plan: spans of `span` positions select their own top-k, one workgroup per unit merges at
@@ -121,11 +121,13 @@ bool bucket_plan(const sparq_shape* s, size_t lds_max, PlanInfo* p) {
   return true;
 }
 
-// The grouped-query rule over several workgroups per KV unit: n1 spans for the logits (about 512 workgroups,
+// The grouped-query rule over several workgroups per KV unit: n1 spans for the logits (at most 256 workgroups,
 // at least 1024 positions each), spans of 4096 / 8192 positions for the two-level selection.
 bool shared_split_plan(const sparq_shape* s, size_t lds_max, PlanInfo* p) {
   const int64_t ukv = (int64_t)s->B * s->H_kv;
-  int64_t n1 = 512 / ukv;
+  // (gs_logits with 4 heads' accumulators runs one workgroup per CU: more than 256 workgroups would come in two
+  // rounds, which was measured as 58 instead of 47 us per decode just above S = 32768 with 8 KV units)
+  int64_t n1 = 256 / ukv;
   if (n1 > kMaxSpans) n1 = kMaxSpans;
   if (n1 < 1) n1 = 1;
   int64_t span1 = (s->S_max + n1 - 1) / n1;
@@ -142,6 +144,24 @@ bool shared_split_plan(const sparq_shape* s, size_t lds_max, PlanInfo* p) {
   if (n > s->k / 64) n = s->k / 64;
   if (n < 1) n = 1;
   p->n1 = (int)n1; p->span1 = (int)span1; p->n_span = (int)n2; p->span_len = span2; p->cand_cap = cap; p->n_split = (int)n;
+  return true;
+}
+
+// The grouped-query rule on the digit-bucket plan: gs_logits over n1 spans per KV unit (at most 256 workgroups, at
+// least 1024 positions each), then the bucket plan's spans for the selection.
+bool shared_bucket_plan(const sparq_shape* s, size_t lds_max, PlanInfo* p) {
+  const int64_t ukv = (int64_t)s->B * s->H_kv;
+  int64_t n1 = 256 / ukv;                   // one round of gs_logits workgroups, as above
+  if (n1 > kMaxSpans) n1 = kMaxSpans;
+  if (n1 < 1) n1 = 1;
+  int64_t span1 = (s->S_max + n1 - 1) / n1;
+  if (span1 < 1024) span1 = 1024;
+  span1 = (span1 + 63) / 64 * 64;
+  n1 = (s->S_max + span1 - 1) / span1;
+  if (n1 > kMaxSpans) return false;
+  if (!bucket_plan(s, lds_max, p)) return false;
+  if (bk_group_scores_lds_bytes(p->span_len) > lds_max) return false;
+  p->n1 = (int)n1; p->span1 = (int)span1;
   return true;
 }
 
@@ -165,6 +185,12 @@ PlanInfo choose_plan(const sparq_shape* s) {
     // S = 8192) and far slower below (230 vs 70 us at 8 units, S = 32768)
     const int64_t ukv = (int64_t)s->B * s->H_kv;
     const bool few = (ukv <= 32 && s->S_max >= 8192) || (ukv <= 64 && s->S_max >= 16384);
+    // few heads with long caches: the digit-bucket selection, one for the group (measured against the two-level
+    // selection per KV head: 59 vs 87 us at 8 KV units, S = 32768; 107 vs 166 us at S = 131072)
+    if ((few || !one_wg) && (int64_t)s->B * s->H <= kSplitMaxUnits && s->S_max >= 8192 && shared_bucket_plan(s, lds_max, &p)) {
+      p.plan = kPlanSharedBucket;
+      return p;
+    }
     if ((few || !one_wg) && shared_split_plan(s, lds_max, &p)) { p.plan = kPlanSharedSplit; return p; }
     if (one_wg) p.plan = kPlanShared;
     return p;
@@ -196,7 +222,7 @@ GsLayout gs_layout(const sparq_shape* s, const PlanInfo& p) {
   return l;
 }
 
-struct BucketLayout { size_t tmax, zsum, anum, tau, zden, coarse, fine, skey, spos, part, end; };
+struct BucketLayout { size_t tmax, zsum, anum, tau, zden, coarse, fine, skey, spos, part, z, stat, esc, end; };
 
 BucketLayout bucket_layout(const sparq_shape* s, const PlanInfo& p) {
   const size_t units = (size_t)s->B * s->H, slots = units * p.n_span;
@@ -212,6 +238,13 @@ BucketLayout bucket_layout(const sparq_shape* s, const PlanInfo& p) {
   l.skey = off; off = align256(off + slots * p.span_len * sizeof(uint32_t));
   l.spos = off; off = align256(off + slots * p.span_len * sizeof(uint32_t));
   l.part = off; off = align256(off + slots * (s->d_h + 2) * sizeof(float));
+  l.z = l.stat = l.esc = off;
+  if (p.plan == kPlanSharedBucket) {      // what gs_logits hands on: logit numerators, span statistics, temperatures
+    const size_t ukv = (size_t)s->B * s->H_kv, g = (size_t)(s->H / s->H_kv);
+    l.z = off; off = align256(off + units * s->S_max * sizeof(float));
+    l.stat = off; off = align256(off + ukv * p.n1 * g * 2 * sizeof(float));
+    l.esc = off; off = align256(off + units * sizeof(float));
+  }
   l.end = off;
   return l;
 }
@@ -242,7 +275,7 @@ size_t workspace_need(const sparq_shape* s) {
   const PlanInfo p = choose_plan(s);
   size_t e = 0;
   if (p.plan == kPlanLong) e = long_layout(s, p).end;
-  if (p.plan == kPlanBucket) e = bucket_layout(s, p).end;
+  if (p.plan == kPlanBucket || p.plan == kPlanSharedBucket) e = bucket_layout(s, p).end;
   if (p.plan == kPlanShared) e = (size_t)kControlBytes + (size_t)s->B * s->H * s->S_max * sizeof(float);
   if (p.plan == kPlanSharedSplit) e = gs_layout(s, p).end;
 #ifdef SPARQ_STAGE_CLOCKS
@@ -270,8 +303,8 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
   if (p.plan == kPlanFused) return launch_decode(a, shape->dtype, s);
   const bool one_k = p.plan == kPlanSingleK;
   DecodeArgs d = a;
-  if (a.k_new && p.plan != kPlanBucket) {
-    // the one-workgroup-per-head kernel and the digit-bucket plan have the append built in; the other plans
+  if (a.k_new && p.plan != kPlanBucket && p.plan != kPlanSharedBucket) {
+    // the one-workgroup-per-head kernel and the digit-bucket plans have the append built in; the other plans
     // append into the *_next state with the append kernel, then decode from that state
     AppendArgs ap;
     ap.K = a.K; ap.Kt = one_k ? nullptr : a.Kt; ap.V = a.V; ap.v_mean = const_cast<float*>(a.v_mean); ap.seq_lens = const_cast<int32_t*>(a.seq_lens);
@@ -304,7 +337,7 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
     ga.part_ws = reinterpret_cast<float*>(w + l.part);
     return launch_decode_shared_split(ga, shape->dtype, s);
   }
-  if (p.plan == kPlanBucket) {
+  if (p.plan == kPlanBucket || p.plan == kPlanSharedBucket) {
     const BucketLayout l = bucket_layout(shape, p);
     BucketArgs ba;
     ba.d = d;
@@ -319,6 +352,19 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
     ba.skey_ws = reinterpret_cast<uint32_t*>(w + l.skey);
     ba.spos_ws = reinterpret_cast<uint32_t*>(w + l.spos);
     ba.part_ws = reinterpret_cast<float*>(w + l.part);
+    if (p.plan == kPlanSharedBucket) {
+      GsArgs ga{};
+      ga.d = d;
+      ga.n1 = p.n1; ga.span1 = p.span1;
+      ga.z_ws = reinterpret_cast<float*>(w + l.z);
+      ga.stat_ws = reinterpret_cast<float*>(w + l.stat);
+      ga.esc_ws = reinterpret_cast<float*>(w + l.esc);
+      hipError_t e = launch_group_logits(ga, shape->dtype, s);
+      if (e != hipSuccess) return e;
+      ba.group = shape->H / shape->H_kv; ba.n1 = p.n1;
+      ba.z_ws = ga.z_ws; ba.stat_ws = ga.stat_ws; ba.esc_ws = ga.esc_ws;
+      return launch_decode_bucket_group(ba, shape->dtype, s);
+    }
     return launch_decode_bucket(ba, shape->dtype, s);
   }
   if (p.plan == kPlanLong) {
@@ -517,6 +563,7 @@ const char* sparq_decode_plan(const sparq_shape* shape) {
     case kPlanLong: return "long_scores + long_merge + split_gather + split_combine (two-level selection plan)";
     case kPlanBucket: return "bk_scores + bk_select_gather + bk_combine (digit-bucket plan)";
     case kPlanShared: return "sparq_decode_shared (grouped-query rule, one workgroup per KV head)";
+    case kPlanSharedBucket: return "gs_logits + bk_group_scores + bk_select_gather + bk_combine (grouped-query rule on the digit-bucket plan)";
     case kPlanSharedSplit: return "gs_logits + gs_select + gs_merge + gs_gather + split_combine (grouped-query rule, several workgroups per KV head)";
     case kPlanSingleK: return "sparq_decode_single_k (key cache stored once)";
     default: return "unsupported";

@@ -78,6 +78,19 @@ __device__ __forceinline__ void find_threshold_bin(const uint32_t* hist, int nee
   }
 }
 
+// The length a launch of a multi-launch plan works on.  Inside sparq_decode_step (d.k_new set) the row being appended counts as position
+// S_b although it reaches the cache only in the plan's last launch: every launch adds it the same way.
+__device__ __forceinline__ int visible_length(const DecodeArgs& d, int b, bool& appended, bool& bad, bool& full) {
+  int S = d.seq_lens[b];
+  bad = S < 0 || S > d.S_max;
+  if (bad) S = S < 0 ? 0 : d.S_max;
+  appended = false; full = false;
+  if (d.k_new) {
+    if (S + 1 <= d.S_max) { appended = true; S += 1; } else full = true;
+  }
+  return S;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Step 1a: the r largest components of |q| (ties to the lower channel) and the temperature (Eq. 9)
 

@@ -25,6 +25,26 @@ __device__ __forceinline__ float group_score(const float (&d)[G], const float (&
   return mx + log2f(s);
 }
 
+// Per-head softmax statistics of a whole sequence from the n1 span partials {max, sum-exp relative to it}:
+// executed by wave 0 (one lane per span, n1 <= 64); results to out[h] = {max, 1 / sum-exp}.
+template <int G>
+__device__ __forceinline__ void combine_span_stats(const float* stat_unit, int n1, const float* esc_unit, int lane, float* out) {
+  const bool on = lane < n1;
+  float m[G], z[G], esc[G];
+#pragma unroll
+  for (int h = 0; h < G; ++h) {      // all loads first: one round trip
+    m[h] = on ? stat_unit[(lane * G + h) * 2] : -INFINITY;
+    z[h] = on ? stat_unit[(lane * G + h) * 2 + 1] : 0.0f;
+    esc[h] = esc_unit[h];
+  }
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    const float m_all = wave_max(m[h]);
+    const float z_all = wave_sum(m[h] == -INFINITY ? 0.0f : z[h] * exp2f((m[h] - m_all) * esc[h]));
+    if (lane == 0) { out[h * 2] = m_all; out[h * 2 + 1] = 1.0f / z_all; }
+  }
+}
+
 struct GroupQueryLds {
   int* rankp;      // [NT] partial ranks
   float* qf;       // [G][DH] the group's queries as fp32

@@ -111,6 +111,13 @@ struct BucketArgs {
   uint32_t* skey_ws;       // [B * H][n_span][span_len] the span's keys sorted by first digit, descending
   uint32_t* spos_ws;       // [B * H][n_span][span_len] their positions
   float* part_ws;          // [B * H][n_span][d_h + 2] attention partials of the spans
+  // the grouped-query rule on this plan (group > 0): one selection per KV head from the group score; the tables
+  // and sorted arrays are indexed by KV unit, the logits and per-head statistics come from gs_logits
+  int32_t group = 0;       // query heads per KV head, 0 = every head selects for itself
+  int32_t n1 = 0;          // logit spans per KV unit of gs_logits
+  const float* z_ws = nullptr;      // [B * H][S_max] logit numerators
+  const float* stat_ws = nullptr;   // [B * H_kv][n1][group][2] span maximum and sum-exp per head
+  const float* esc_ws = nullptr;    // [B * H] log2(e) / tau
 };
 
 // LDS bytes the fused decode kernel needs for a cache of S_max rows and head dimension d_h
@@ -127,6 +134,12 @@ size_t bk_scores_lds_bytes(int span_len, int d_h);
 size_t bk_select_lds_bytes(int span_len, int d_h, int n_span, int cand_cap);
 int bk_fine_len();
 hipError_t launch_decode_bucket(const BucketArgs& a, int dtype, hipStream_t s);
+size_t bk_group_scores_lds_bytes(int span_len);
+// the grouped-query rule on the digit-bucket plan: after gs_logits (launch_group_logits), uses a.group, n1, z_ws, stat_ws, esc_ws
+hipError_t launch_decode_bucket_group(const BucketArgs& a, int dtype, hipStream_t s);
+// the first launch of the grouped-query plans alone: logit numerators and per-head span statistics (uses d, n1, span1,
+// z_ws, stat_ws, esc_ws of `a`)
+hipError_t launch_group_logits(const GsArgs& a, int dtype, hipStream_t s);
 // the gather launch and the merge (gather over slices of list_ws, merge): uses d, n_split,
 // alpha_ws, list_ws, part_ws of `a`
 hipError_t launch_split_gather(const SplitArgs& a, int dtype, hipStream_t s);

@@ -20,9 +20,12 @@
 // Every workgroup attends over the selected rows of its own span: the gather is balanced when the selected
 // positions are spread over the sequence, and takes as long as the busiest span when they are not.
 // The local window is part of it: its positions count as digit 2047, above every finite key.
+// The grouped-query rule runs on the same plan: gs_logits leaves every head's logit numerators and statistics in
+// the workspace, bk_group_scores turns the group score into keys and publishes the spans per KV unit, and
+// bk_select_gather<GROUP> / bk_combine run per query head on the KV unit's tables (alpha from the head's own logits).
 // Inside sparq_decode_step the three launches count the row being appended as position S_b (taken from the
 // inputs wherever it is needed) and bk_combine writes it to the cache, after every read of the earlier launches.
-#include "decode_stages.h"
+#include "group_stages.h"
 
 namespace sparq {
 
@@ -44,17 +47,65 @@ __device__ __forceinline__ void map_span(int U, int n_span, int& u, int& s) {
   }
 }
 
-// The length a launch works on.  Inside sparq_decode_step (d.k_new set) the row being appended counts as position
-// S_b although it reaches the cache only in the plan's last launch: every launch adds it the same way.
-__device__ __forceinline__ int visible_length(const DecodeArgs& d, int b, bool& appended, bool& bad, bool& full) {
-  int S = d.seq_lens[b];
-  bad = S < 0 || S > d.S_max;
-  if (bad) S = S < 0 ? 0 : d.S_max;
-  appended = false; full = false;
-  if (d.k_new) {
-    if (S + 1 <= d.S_max) { appended = true; S += 1; } else full = true;
+// The bucket of a key.  Ordinary keys (approximate logits): their first 11 bits.  Group-score keys are
+// log2 of a sum of probabilities, x <= 2, often down to -1000: their first 11 bits (sign, exponent, two mantissa
+// bits) tell 20-30 values apart and thousands of keys would share the threshold's bucket.  For them the bucket
+// comes from u = 4 - x >= 2 instead: 4 exponent bits and 7 mantissa bits of u (128 buckets per octave of u),
+// counted down so that a larger score has a larger digit.  Both maps are monotone in the key, which is all the
+// selection needs of a bucket (ranking inside the threshold bucket uses the whole key); 2047 stays free.
+template <bool GROUP>
+__device__ __forceinline__ uint32_t bucket_digit(uint32_t key) {
+  if (!GROUP) return key >> 21;
+  const uint32_t bits = __float_as_uint(4.0f - key_to_float(key));   // u > 0 (or +inf): the bits order like u
+  const int e = (int)(bits >> 23) - 128;
+  uint32_t low = e < 0 ? 0u : (e > 15 ? 2046u : ((uint32_t)e << 7) | ((bits >> 16) & 127u));
+  low = low > 2046u ? 2046u : low;
+  return 2046u - low;
+}
+
+// The table A[d] = number of the span's keys whose first digit is >= d, from the first-digit counts in `hist`
+// (swizzled slots): A as u16 to fine[0..2047] (and 32 zeros behind), A[32 l] to coarse[l], and the write cursors
+// of the digit buckets (keys with a larger digit come first) to cur.  One wave: lane l owns digits 32 l .. 32 l + 31.
+__device__ __forceinline__ void build_span_table(const uint32_t* hist, uint32_t* cur, uint16_t* fine, uint16_t* coarse, int lane) {
+  uint32_t cnt[32], mine = 0;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) { cnt[i] = hist[(i << 6) | lane]; mine += cnt[i]; }
+  const uint32_t incl = wave_scan_incl(mine);
+  const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
+  uint32_t run = total - incl;              // keys with digits owned by higher lanes
+  uint32_t packed[16];
+#pragma unroll
+  for (int i = 31; i >= 0; --i) {
+    cur[(i << 6) | lane] = run;             // keys with a digit above 32 l + i
+    run += cnt[i];                          // A[32 l + i]
+    if (i & 1) packed[i >> 1] = run << 16; else packed[i >> 1] |= run;
   }
-  return S;
+  uint4* dst = reinterpret_cast<uint4*>(fine + lane * 32);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) dst[i] = make_uint4(packed[4 * i], packed[4 * i + 1], packed[4 * i + 2], packed[4 * i + 3]);
+  coarse[lane] = (uint16_t)run;             // A[32 l]
+  if (lane < 32) fine[kRadixBins + lane] = 0;
+}
+
+// Counting sort of a span's keys by first digit into LDS (window positions, relative index >= w0, as the top
+// digit; the order inside a bucket is whatever the atomics give: the select only ever uses buckets as sets),
+// then one contiguous copy to the workspace.  Called by the whole workgroup after a barrier behind
+// build_span_table; contains one barrier.
+template <bool GROUP>
+__device__ __forceinline__ void sort_span_by_digit(const uint32_t* keys, int len, int w0, int p0, uint32_t* cur, uint32_t* skey,
+                                                   uint32_t* spos, uint32_t* gkey, uint32_t* gpos, int tid) {
+  for (int i = tid; i < len; i += NT) {
+    const uint32_t key = keys[i];
+    const uint32_t digit = i >= w0 ? (uint32_t)kTopDigit : bucket_digit<GROUP>(key);
+    const uint32_t e = atomicAdd(&cur[hist_slot(digit)], 1u);
+    skey[e] = key;
+    spos[e] = (uint32_t)(p0 + i);
+  }
+  __syncthreads();
+  for (int i = tid * 4; i < len; i += NT * 4) {     // span_len is a multiple of 64: whole 16-byte pieces
+    *reinterpret_cast<uint4*>(gkey + i) = *reinterpret_cast<const uint4*>(skey + i);
+    *reinterpret_cast<uint4*>(gpos + i) = *reinterpret_cast<const uint4*>(spos + i);
+  }
 }
 
 // LDS words of bk_scores besides the three span-sized arrays
@@ -201,27 +252,9 @@ __global__ __launch_bounds__(NT, 4) void bk_scores(const BucketArgs a) {
   for (int w = 1; w < NW; ++w) dmax = fmaxf(dmax, red[w]);
   __syncthreads();     // red is reused below
 
-  // the table A[d] = keys with digit >= d (one wave: lane l owns digits 32 l .. 32 l + 31), the bucket
-  // cursors (keys with a larger digit come first), and the softmax denominator relative to the span's maximum
+  // the table and the bucket cursors (one wave), and the softmax denominator relative to the span's maximum
   if (wave == 0) {
-    uint32_t cnt[32], mine = 0;
-#pragma unroll
-    for (int i = 0; i < 32; ++i) { cnt[i] = hist[(i << 6) | lane]; mine += cnt[i]; }
-    const uint32_t incl = wave_scan_incl(mine);
-    const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, kWave - 1);
-    uint32_t run = total - incl;              // keys with digits owned by higher lanes
-    uint32_t packed[16];
-#pragma unroll
-    for (int i = 31; i >= 0; --i) {
-      cur[(i << 6) | lane] = run;             // keys with a digit above 32 l + i
-      run += cnt[i];                          // A[32 l + i]
-      if (i & 1) packed[i >> 1] = run << 16; else packed[i >> 1] |= run;
-    }
-    uint4* dst = reinterpret_cast<uint4*>(fine + lane * 32);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) dst[i] = make_uint4(packed[4 * i], packed[4 * i + 1], packed[4 * i + 2], packed[4 * i + 3]);
-    coarse[lane] = (uint16_t)run;             // A[32 l]
-    if (lane < 32) fine[kRadixBins + lane] = 0;
+    build_span_table(hist, cur, fine, coarse, lane);
   } else {
     const float esc = kLog2e / tau;
     float z = 0.0f;
@@ -237,22 +270,82 @@ __global__ __launch_bounds__(NT, 4) void bk_scores(const BucketArgs a) {
     a.tmax_ws[slot] = dmax;
     a.zsum_ws[slot] = z;
   }
-  // counting sort by the first digit into LDS (the order inside a bucket is whatever the atomics give:
-  // bk_select only ever uses buckets as sets), then one contiguous copy to the workspace
-  for (int i = tid; i < len; i += NT) {
-    const uint32_t key = keys[i];
-    const uint32_t digit = i >= w0 ? (uint32_t)kTopDigit : key >> 21;
-    const uint32_t e = atomicAdd(&cur[hist_slot(digit)], 1u);
-    skey[e] = key;
-    spos[e] = (uint32_t)(p0 + i);
+  sort_span_by_digit<false>(keys, len, w0, p0, cur, skey, spos, a.skey_ws + slot * P, a.spos_ws + slot * P, tid);
+}
+
+// The grouped-query rule's keys for this plan: one workgroup per (KV unit, span) reads the G logit numerators of
+// every position of its span (left in the workspace by gs_logits, with every head's span maxima and sums), forms
+// the group score sum_h s-hat_h as a key, and publishes the span like bk_scores does (table, sorted arrays),
+// indexed by KV unit: the G query heads of the group share one selection.
+template <int G>
+__global__ __launch_bounds__(NT, 2) void bk_group_scores(const BucketArgs a) {
+  extern __shared__ __align__(16) uint32_t smem[];
+  const int P = a.span_len;
+  uint32_t* keys = smem;
+  uint32_t* skey = keys + P;
+  uint32_t* spos = skey + P;
+  uint32_t* hist = spos + P;
+  uint32_t* cur = hist + kRadixBins;
+  float* hs = reinterpret_cast<float*>(cur + kRadixBins);        // [G][2] max, 1 / sum-exp
+  const DecodeArgs& d = a.d;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int ukv, s;
+  map_span(d.B * d.H_kv, a.n_span, ukv, s);
+  const int b = ukv / d.H_kv, hk = ukv - b * d.H_kv;
+  const size_t u0 = (size_t)b * d.H + (size_t)hk * G;
+  const size_t slot = (size_t)ukv * a.n_span + s;
+  uint16_t* fine = a.fine_ws + slot * kFineLen;
+  uint16_t* coarse = a.coarse_ws + slot * 64;
+  bool appended, bad, full;
+  const int S = visible_length(d, b, appended, bad, full);
+  if (S == 0) return;                      // reported, and the outputs written, by gs_logits
+  int kb = d.k_per_seq ? d.k_per_seq[b] : d.k;
+  kb = kb < 1 ? 1 : (kb > d.k ? d.k : kb);
+  const int kq = kb < S ? kb : S;
+  const Window win = make_window(d.local_window, S, kq);
+  const int p0 = s * P;
+  if (p0 >= S) {   // a span beyond the end of this sequence: an empty table
+    for (int i = tid; i < kFineLen; i += NT) fine[i] = 0;
+    if (tid < 64) coarse[tid] = 0;
+    return;
   }
+  const int len = S - p0 < P ? S - p0 : P;
+  for (int i = tid; i < kRadixBins; i += NT) hist[i] = 0u;
+  if (wave == 0) combine_span_stats<G>(a.stat_ws + (size_t)ukv * a.n1 * G * 2, a.n1, a.esc_ws + u0, lane, hs);
   __syncthreads();
-  uint32_t* gkey = a.skey_ws + slot * P;
-  uint32_t* gpos = a.spos_ws + slot * P;
-  for (int i = tid * 4; i < len; i += NT * 4) {     // span_len is a multiple of 64: whole 16-byte pieces
-    *reinterpret_cast<uint4*>(gkey + i) = *reinterpret_cast<const uint4*>(skey + i);
-    *reinterpret_cast<uint4*>(gpos + i) = *reinterpret_cast<const uint4*>(spos + i);
+  float mh[G], inv_z[G], esc[G];
+#pragma unroll
+  for (int h = 0; h < G; ++h) { mh[h] = hs[h * 2]; inv_z[h] = hs[h * 2 + 1]; esc[h] = a.esc_ws[u0 + h]; }
+  const float* z_unit = a.z_ws + u0 * (size_t)d.S_max + p0;
+  const int n_chunks = (len + 7) >> 3;
+  for (int c = tid; c < n_chunks; c += NT) {
+    float4 lo[G], hi[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      const float4* src = reinterpret_cast<const float4*>(z_unit + (size_t)h * d.S_max + c * 8);
+      lo[h] = src[0]; hi[h] = src[1];
+    }
+    uint32_t kx[8], dg[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float dv[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) dv[h] = e < 4 ? (&lo[h].x)[e] : (&hi[h].x)[e - 4];
+      kx[e] = c * 8 + e < len ? float_to_key(group_score<G>(dv, mh, esc, inv_z)) : 0u;
+      dg[e] = bucket_digit<true>(kx[e]) << 21;      // hist_add_chunk counts by the first 11 bits of what it is given
+    }
+    hist_add_chunk(hist, dg, (win.S_old < p0 + len ? win.S_old : p0 + len) - (p0 + c * 8));
+    uint4* dst = reinterpret_cast<uint4*>(keys + c * 8);
+    dst[0] = make_uint4(kx[0], kx[1], kx[2], kx[3]);
+    dst[1] = make_uint4(kx[4], kx[5], kx[6], kx[7]);
   }
+  // the part of the local window that lies in this span counts as the top digit
+  const int w0 = win.S_old > p0 ? win.S_old - p0 : 0;
+  if (tid == 0 && w0 < len) atomicAdd(&hist[hist_slot(kTopDigit)], (uint32_t)(len - w0));
+  __syncthreads();
+  if (wave == 0) build_span_table(hist, cur, fine, coarse, lane);
+  __syncthreads();
+  sort_span_by_digit<true>(keys, len, w0, p0, cur, skey, spos, a.skey_ws + slot * P, a.spos_ws + slot * P, tid);
 }
 
 // LDS words of bk_select_gather: two span-sized arrays and the bitmap, the candidates (keys sharing the
@@ -265,7 +358,10 @@ __host__ __device__ constexpr size_t bk_select_words(int span_len, int n_span, i
          5 * (kMaxSpans + 8) + NW * (DH + 2) + 32 + 16 + 16;
 }
 
-template <class T, int DH>
+// GROUP = true is the grouped-query rule: the tables and sorted arrays are the KV unit's (one selection for the
+// group's query heads, written by bk_group_scores), the statistics and alpha are the head's own, from the logits
+// gs_logits left in the workspace.
+template <class T, int DH, bool GROUP>
 __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
   extern __shared__ __align__(16) uint32_t smem[];
   const int P = a.span_len;
@@ -292,7 +388,8 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
   map_span(U, a.n_span, u, s);
   const int b = u / d.H, h = u - b * d.H;
   const size_t kv_head = (size_t)b * d.H_kv + h / (d.H / d.H_kv);
-  const size_t slot0 = (size_t)u * a.n_span, slot = slot0 + s;
+  const size_t slot = (size_t)u * a.n_span + s;                       // this workgroup's partial and numerator
+  const size_t slot0 = (GROUP ? kv_head : (size_t)u) * a.n_span;      // the spans whose tables and sorted arrays it reads
   using G = RowGeometry<DH>;
   const int sub = lane % G::LPR;
 
@@ -302,7 +399,7 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
   const int S = visible_length(d, b, appended, bad, full);
   int kb = d.k_per_seq ? d.k_per_seq[b] : d.k;
   const uint4 qraw = load16(reinterpret_cast<const uint16_t*>(d.q) + (size_t)u * DH + sub * 8);
-  const float tau = a.tau_ws[u];
+  const float esc = GROUP ? a.esc_ws[u] : kLog2e / a.tau_ws[u];
   uint32_t v[kMaxSpans / NW];
 #pragma unroll
   for (int j = 0; j < kMaxSpans / NW; ++j) {
@@ -310,7 +407,12 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
     v[j] = t < a.n_span ? a.coarse_ws[(slot0 + t) * 64 + lane] : 0u;
   }
   float tm = -INFINITY, zs = 0.0f;
-  if (wave == 1 && lane < a.n_span) { tm = a.tmax_ws[slot0 + lane]; zs = a.zsum_ws[slot0 + lane]; }
+  if (GROUP) {         // this head's maximum and sum-exp over each of gs_logits' spans
+    const float* st = a.stat_ws + ((kv_head * a.n1 + lane) * a.group + (h % a.group)) * 2;
+    if (wave == 1 && lane < a.n1) { tm = st[0]; zs = st[1]; }
+  } else if (wave == 1 && lane < a.n_span) {
+    tm = a.tmax_ws[slot0 + lane]; zs = a.zsum_ws[slot0 + lane];
+  }
 
   if (S == 0) return;                      // outputs written by bk_scores
   kb = kb < 1 ? 1 : (kb > d.k ? d.k : kb);
@@ -328,7 +430,6 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
     return;
   }
   const int len = S - p0 < P ? S - p0 : P;
-  const float esc = kLog2e / tau;
 
   // ---- the threshold digit d0: the largest d with N(d) = sum over spans of A_s[d] >= kq ----
   for (int i = tid; i < kRadixBins; i += NT) hist[i] = 0u;
@@ -391,8 +492,8 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
 
   // this span's own entries above or in the threshold digit: the first four per thread are requested now,
   // together with the candidates, and looked at after the ranking
-  const uint32_t* gkey = a.skey_ws + slot * P;
-  const uint32_t* gpos = a.spos_ws + slot * P;
+  const uint32_t* gkey = a.skey_ws + (slot0 + s) * P;
+  const uint32_t* gpos = a.spos_ws + (slot0 + s) * P;
   const int n_above = a_s[s], n_mine = n_above + c_s[s];
   uint32_t okey[4], opos[4];
 #pragma unroll
@@ -432,8 +533,8 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
     }
     __syncthreads();
   }
-  // a candidate as one 41-bit number: the 21 key bits below the first digit, then the position counted
-  // down from the top, so that "larger" is "larger key, or equal key and lower position"; t = its span
+  // a candidate as one number: the 21 key bits below the first digit (group-score keys: all 32), then the position
+  // counted down from the top, so that "larger" is "larger key, or equal key and lower position"; t = its span
   auto candidate = [&](int i, int& t) -> uint64_t {
     uint32_t key, pos;
     if (resident) {
@@ -444,17 +545,20 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
       key = a.skey_ws[(slot0 + t) * P + e];
       pos = a.spos_ws[(slot0 + t) * P + e];
     }
-    return ((uint64_t)(key & 0x1fffffu) << 20) | (uint64_t)(kPosMask - pos);
+    return ((uint64_t)(GROUP ? key : key & 0x1fffffu) << 20) | (uint64_t)(kPosMask - pos);
   };
 
-  // ---- exact rank among the candidates: radix passes of 11, 10, 10 and 10 bits; stop as soon as the
-  // remaining bin is taken whole (with distinct keys: after the key bits) ----
+  // ---- exact rank among the candidates: radix passes of 11, 10, 10 and 10 bits (group-score keys, whose bucket
+  // is not their first digit: the whole key, one more pass of 11 bits in front); stop as soon as the remaining bin
+  // is taken whole (with distinct keys: after the key bits) ----
   uint64_t mask = 0, thr = 0;
   if (need < C0) {
     int in_bin = C0;
-    for (int pass = 0; pass < 4 && need < in_bin; ++pass) {
-      const int shift = 30 - 10 * pass;
-      const uint32_t dmask = pass == 0 ? 0x7ffu : 0x3ffu;
+    constexpr int kPasses = GROUP ? 5 : 4;
+    for (int pass = 0; pass < kPasses && need < in_bin; ++pass) {
+      const int lead = kPasses - 4;                // passes of 11 bits before the last three of 10
+      const int shift = pass <= lead ? 30 + 11 * (lead - pass) : 30 - 10 * (pass - lead);
+      const uint32_t dmask = pass <= lead ? 0x7ffu : 0x3ffu;
       if (pass > 0) {
         for (int i = tid; i < kRadixBins; i += NT) hist[i] = 0u;
         __syncthreads();
@@ -496,7 +600,7 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
   auto mark = [&](int e, uint32_t key, uint32_t pos) {
     bool take = e < n_above;
     if (!take) {
-      const uint64_t c = ((uint64_t)(key & 0x1fffffu) << 20) | (uint64_t)(kPosMask - pos);
+      const uint64_t c = ((uint64_t)(GROUP ? key : key & 0x1fffffu) << 20) | (uint64_t)(kPosMask - pos);
       take = (c & mask) >= thr;
     }
     if (take) {
@@ -522,8 +626,13 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
     const int rel = tid * 32 + bit;
     list[o] = p0 + rel;
     if (idx_out && offs[s] + (int)o < d.idx_stride) idx_out[offs[s] + o] = p0 + rel;
-    anum += exp2f((key_to_float(keyval[rel]) - gmax) * esc);
+    if (!GROUP) anum += exp2f((key_to_float(keyval[rel]) - gmax) * esc);
     ++o;
+  }
+  if (GROUP) {         // this head's own approximate scores of the selected positions, from its stored logits
+    __syncthreads();   // the list
+    const float* z_head = a.z_ws + (size_t)u * d.S_max;
+    for (int n = tid; n < (int)total; n += NT) anum += exp2f((z_head[list[n]] - gmax) * esc);
   }
   anum = wave_sum(anum);
   if (lane == 0) red[wave] = anum;
@@ -640,16 +749,43 @@ hipError_t launch_bucket(const BucketArgs& a, hipStream_t s) {
   const size_t lds1 = bk_scores_lds_bytes(a.span_len, DH), lds2 = bk_select_lds_bytes(a.span_len, DH, a.n_span, a.cand_cap);
   hipError_t e;
   if ((e = allow_lds<bk_scores<T, DH>>(lds1)) != hipSuccess) return e;
-  if ((e = allow_lds<bk_select_gather<T, DH>>(lds2)) != hipSuccess) return e;
+  if ((e = allow_lds<bk_select_gather<T, DH, false>>(lds2)) != hipSuccess) return e;
   hipLaunchKernelGGL((bk_scores<T, DH>), dim3(units * a.n_span), dim3(NT), lds1, s, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL((bk_select_gather<T, DH>), dim3(units * a.n_span), dim3(NT), lds2, s, a);
+  hipLaunchKernelGGL((bk_select_gather<T, DH, false>), dim3(units * a.n_span), dim3(NT), lds2, s, a);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL((bk_combine<T, DH>), dim3(units), dim3(DH), 0, s, a);
+  return hipGetLastError();
+}
+
+// the grouped-query rule: the keys come from the group's stored logits, the rest is the same two launches
+template <class T, int DH>
+hipError_t launch_bucket_group(const BucketArgs& a, hipStream_t s) {
+  const int units = a.d.B * a.d.H, ukv = a.d.B * a.d.H_kv;
+  const size_t lds1 = bk_group_scores_lds_bytes(a.span_len), lds2 = bk_select_lds_bytes(a.span_len, DH, a.n_span, a.cand_cap);
+  hipError_t e;
+  if ((e = allow_lds<bk_select_gather<T, DH, true>>(lds2)) != hipSuccess) return e;
+  switch (a.group) {
+    case 2:
+      if ((e = allow_lds<bk_group_scores<2>>(lds1)) != hipSuccess) return e;
+      hipLaunchKernelGGL(bk_group_scores<2>, dim3(ukv * a.n_span), dim3(NT), lds1, s, a);
+      break;
+    case 4:
+      if ((e = allow_lds<bk_group_scores<4>>(lds1)) != hipSuccess) return e;
+      hipLaunchKernelGGL(bk_group_scores<4>, dim3(ukv * a.n_span), dim3(NT), lds1, s, a);
+      break;
+    default: return hipErrorInvalidValue;
+  }
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL((bk_select_gather<T, DH, true>), dim3(units * a.n_span), dim3(NT), lds2, s, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL((bk_combine<T, DH>), dim3(units), dim3(DH), 0, s, a);
   return hipGetLastError();
 }
 
 }  // namespace
+
+size_t bk_group_scores_lds_bytes(int span_len) { return 4 * (3 * (size_t)span_len + 2 * kRadixBins + 16); }
 
 size_t bk_scores_lds_bytes(int span_len, int d_h) {
   switch (d_h) {
@@ -677,6 +813,16 @@ hipError_t launch_decode_bucket(const BucketArgs& a, int dtype, hipStream_t s) {
     case 64:  return bf ? launch_bucket<BF16, 64>(a, s) : launch_bucket<F16, 64>(a, s);
     case 128: return bf ? launch_bucket<BF16, 128>(a, s) : launch_bucket<F16, 128>(a, s);
     case 256: return bf ? launch_bucket<BF16, 256>(a, s) : launch_bucket<F16, 256>(a, s);
+    default:  return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_decode_bucket_group(const BucketArgs& a, int dtype, hipStream_t s) {
+  const bool bf = dtype == 1;
+  switch (a.d.d_h) {
+    case 64:  return bf ? launch_bucket_group<BF16, 64>(a, s) : launch_bucket_group<F16, 64>(a, s);
+    case 128: return bf ? launch_bucket_group<BF16, 128>(a, s) : launch_bucket_group<F16, 128>(a, s);
+    case 256: return bf ? launch_bucket_group<BF16, 256>(a, s) : launch_bucket_group<F16, 256>(a, s);
     default:  return hipErrorInvalidValue;
   }
 }

@@ -28,26 +28,6 @@ __device__ __forceinline__ void map_kv(int Ukv, int n, int& ukv, int& s) {
   }
 }
 
-// Per-head softmax statistics of a whole sequence from the n1 span partials {max, sum-exp relative to it}:
-// executed by wave 0 (one lane per span, n1 <= 64); results to out[h] = {max, 1 / sum-exp}.
-template <int G>
-__device__ __forceinline__ void combine_span_stats(const float* stat_unit, int n1, const float* esc_unit, int lane, float* out) {
-  const bool on = lane < n1;
-  float m[G], z[G], esc[G];
-#pragma unroll
-  for (int h = 0; h < G; ++h) {      // all loads first: one round trip
-    m[h] = on ? stat_unit[(lane * G + h) * 2] : -INFINITY;
-    z[h] = on ? stat_unit[(lane * G + h) * 2 + 1] : 0.0f;
-    esc[h] = esc_unit[h];
-  }
-#pragma unroll
-  for (int h = 0; h < G; ++h) {
-    const float m_all = wave_max(m[h]);
-    const float z_all = wave_sum(m[h] == -INFINITY ? 0.0f : z[h] * exp2f((m[h] - m_all) * esc[h]));
-    if (lane == 0) { out[h * 2] = m_all; out[h * 2 + 1] = 1.0f / z_all; }
-  }
-}
-
 template <class T, int DH, int G>
 __global__ __launch_bounds__(NT, 2) void gs_logits(const GsArgs a) {
   __shared__ int rankp[NT];
@@ -61,11 +41,9 @@ __global__ __launch_bounds__(NT, 2) void gs_logits(const GsArgs a) {
   map_kv(d.B * d.H_kv, a.n1, ukv, s);
   const int b = ukv / d.H_kv, hk = ukv - b * d.H_kv;
   const size_t u0 = (size_t)b * d.H + (size_t)hk * G;
-  int S = d.seq_lens[b];
-  if (S < 0 || S > d.S_max) {
-    if (tid == 0 && s == 0) atomicOr(d.err, 8);
-    S = S < 0 ? 0 : d.S_max;
-  }
+  bool appended, bad, full;      // inside a step of the digit-bucket plan the row being appended counts as position S_b
+  const int S = visible_length(d, b, appended, bad, full);
+  if (tid == 0 && s == 0 && (bad || full)) atomicOr(d.err, (bad ? 8 : 0) | (full ? 1 : 0));
   if (S == 0) {   // nothing cached: part 0 writes the defined outputs, the later launches skip the unit
     if (s == 0) {
       uint16_t* out = reinterpret_cast<uint16_t*>(d.out) + u0 * DH;
@@ -98,16 +76,14 @@ __global__ __launch_bounds__(NT, 2) void gs_logits(const GsArgs a) {
 
   // the newest S mod 8 positions are not in Kt: the span that holds them takes them from the rows of K
   const size_t kv_head = (size_t)ukv;
-  const int S_fl = S & ~7, r8 = (d.r + 7) & ~7;
+  const int S_fl = (appended ? S - 1 : S) & ~7, r8 = (d.r + 7) & ~7;
   const int n_tail = (S_fl >= p0 && S_fl < p0 + len) ? S - S_fl : 0;
-  float tdot[G];
-#pragma unroll
-  for (int h = 0; h < G; ++h) tdot[h] = 0.0f;
+  TailRow tail;                  // requested here, used after the stream
   if (wave < n_tail) {
-    const TailRow tail = tail_row_issue(reinterpret_cast<const uint16_t*>(d.K) + (kv_head * d.S_max + S_fl + wave) * (size_t)DH,
-                                        chan, r8, lane);
-#pragma unroll
-    for (int h = 0; h < G; ++h) tdot[h] = tail_row_dot<T>(tail, qs + h * DH, r8, lane);
+    const uint16_t* krow = appended && wave == n_tail - 1
+                               ? reinterpret_cast<const uint16_t*>(d.k_new) + kv_head * DH
+                               : reinterpret_cast<const uint16_t*>(d.K) + (kv_head * d.S_max + S_fl + wave) * (size_t)DH;
+    tail = tail_row_issue(krow, chan, r8, lane);
   }
 
   const int end = p0 + len < S_fl ? p0 + len : S_fl;     // whole chunks of this span that are in Kt
@@ -132,6 +108,9 @@ __global__ __launch_bounds__(NT, 2) void gs_logits(const GsArgs a) {
       }
     }
   });
+  float tdot[G];
+#pragma unroll
+  for (int h = 0; h < G; ++h) tdot[h] = wave < n_tail ? tail_row_dot<T>(tail, qs + h * DH, r8, lane) : 0.0f;
   if (wave < n_tail && lane == 0) {
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -514,6 +493,29 @@ size_t gs_select_lds_bytes(int span2) { return 4 * ((size_t)span2 + 2 * kRadixBi
 
 size_t gs_merge_lds_bytes(int n2, int cand_cap) {
   return 4 * ((((size_t)n2 * cand_cap + 7) & ~(size_t)7) + 2 * kRadixBins + 32 + 16 + 8 + kMaxSpans + 8 + 8 + NW * 4);
+}
+
+namespace {
+template <class T, int DH>
+hipError_t launch_logits_dh(const GsArgs& a, hipStream_t s) {
+  const int Ukv = a.d.B * a.d.H_kv;
+  switch (a.d.H / a.d.H_kv) {
+    case 2: hipLaunchKernelGGL((gs_logits<T, DH, 2>), dim3(Ukv * a.n1), dim3(NT), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((gs_logits<T, DH, 4>), dim3(Ukv * a.n1), dim3(NT), 0, s, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_group_logits(const GsArgs& a, int dtype, hipStream_t s) {
+  const bool bf = dtype == 1;
+  switch (a.d.d_h) {
+    case 64:  return bf ? launch_logits_dh<BF16, 64>(a, s) : launch_logits_dh<F16, 64>(a, s);
+    case 128: return bf ? launch_logits_dh<BF16, 128>(a, s) : launch_logits_dh<F16, 128>(a, s);
+    case 256: return bf ? launch_logits_dh<BF16, 256>(a, s) : launch_logits_dh<F16, 256>(a, s);
+    default:  return hipErrorInvalidValue;
+  }
 }
 
 hipError_t launch_decode_shared_split(const GsArgs& a, int dtype, hipStream_t s) {

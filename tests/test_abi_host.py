@@ -101,7 +101,7 @@ def test_shapes_without_a_kernel_are_refused_before_any_launch():
     refused = [
         dict(S_max=1 << 20, k=64),                                   # more than 64 spans of 8192
         dict(S_max=262144, k=2048, B=8, H=32, H_kv=32),               # many heads: 32 spans x 2048 candidates do not fit in LDS
-        dict(S_max=262144, k=2048, flags=B.SPARQ_FLAG_GQA_SHARED),   # the same limit under the grouped-query rule
+        dict(S_max=262144, k=2048, B=8, H=32, H_kv=8, flags=B.SPARQ_FLAG_GQA_SHARED),   # the same limit under the grouped-query rule
         dict(S_max=65536, flags=B.SPARQ_FLAG_SINGLE_K, H=2, H_kv=2),
         dict(H=8, H_kv=1, flags=B.SPARQ_FLAG_GQA_SHARED),            # groups of 8 query heads
         dict(flags=B.SPARQ_FLAG_GQA_SHARED | B.SPARQ_FLAG_SINGLE_K),
@@ -112,6 +112,8 @@ def test_shapes_without_a_kernel_are_refused_before_any_launch():
         assert call_decode(shape(**kw), good) == B.SPARQ_EUNSUPPORTED, kw
     # with few heads the digit-bucket plan has no candidate limit: the same length is served
     assert call_decode(shape(S_max=262144, k=2048), good) in (B.SPARQ_OK, B.SPARQ_ELAUNCH)
+    assert call_decode(shape(S_max=262144, k=2048, flags=B.SPARQ_FLAG_GQA_SHARED), good) in (B.SPARQ_OK, B.SPARQ_ELAUNCH)
+    assert "digit-bucket" in B.sparq_decode_plan(shape(S_max=262144, k=2048, flags=B.SPARQ_FLAG_GQA_SHARED))
     # sizes that the multi-launch plans do serve still get a workspace size (and grow with S_max)
     a = B.sparq_workspace_bytes(shape(S_max=131072, k=2048, H=2, H_kv=2))
     b = B.sparq_workspace_bytes(shape(S_max=65536, k=2048, H=2, H_kv=2))

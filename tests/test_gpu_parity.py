@@ -238,6 +238,8 @@ def test_unsupported_requests_are_refused():
     ("g2_split_40k_d256", dict(B=1, H=4, H_kv=2, d_h=256, S=40003, r=64, k=1024, dtype="bf16"), 0.005),
     ("g4_split_70k", dict(B=1, H=4, H_kv=1, d_h=128, S=70000, r=32, k=2048, dtype="bf16"), 0.02),
     ("g2_split_d64", dict(B=3, H=2, H_kv=1, d_h=64, S=17000, r=8, k=64, dtype="f16"), 0.05),
+    # more than 128 query heads on few KV heads: the two-level selection per KV head
+    ("g4_split_many_heads", dict(B=9, H=16, H_kv=4, d_h=64, S=16500, r=16, k=200, dtype="f16"), 0.05),
 ])
 def test_grouped_query_shared_selection(name, kw, qs):
     """SPARQ_FLAG_GQA_SHARED: one channel set and one position set per KV head from the group sums
@@ -285,6 +287,58 @@ def test_grouped_query_shared_step_and_ties():
     assert torch.equal(idx.cpu(), torch.arange(50, dtype=torch.int32).expand(1, 4, 50))
     assert torch.allclose(alpha.cpu(), torch.full((1, 4), 0.1), atol=1e-6)
     Hn.compare_decode(t, q, flags=B.SPARQ_FLAG_GQA_SHARED)
+
+
+def test_grouped_query_rule_on_the_digit_bucket_plan_steps_and_ties():
+    """The grouped-query rule for few heads with long caches (one digit-bucket selection per KV head): several
+    one-call steps with ragged lengths, so that the new row lands in different places of a group of 8 positions and
+    once completes it (state and outputs against append + decode and the oracle), and all-identical keys."""
+    w = W.Workload("g4_bucket_step", 2, 8, 2, 128, 9000, 16, 300, "bf16", seed=53)
+    FL = B.SPARQ_FLAG_GQA_SHARED
+    assert "grouped-query rule on the digit-bucket plan" in B.sparq_decode_plan(B.make_shape(w.B, w.H, w.H_kv, 9024, w.d_h, w.r, w.k, w.dtype_code, FL))
+    seq = torch.tensor([8997, 8400], dtype=torch.int32)
+    steps = 4
+    a = Hn.build_cache(w, seq_lens=seq, S_max=9024, v_offset=True, flags=FL)     # separate calls
+    f = Hn.build_cache(w, seq_lens=seq, S_max=9024, v_offset=True, flags=FL)     # the one-call step
+    kn, vn = W.draw_kv(W.scaled(w, seed=54), "cuda", n_rows=steps, v_offset=True)
+    cur = seq.clone()
+    Kg, Vg = torch.cat([a.K_src, kn], dim=2).clone(), torch.cat([a.V_src, vn], dim=2).clone()
+    for t in range(steps):
+        k_t, v_t = kn[:, :, t].contiguous(), vn[:, :, t].contiguous()
+        q = W.draw_queries(w, a.cache.K, cur, n=1, q_scale=0.02, stream=t)[0]
+        if t == 1:          # make the new row the best match for the first group so that it is certainly selected
+            q[:, 0:4] = (k_t[:, 0:1].float() * 0.05).to(q.dtype)
+        a.cache.append(k_t, v_t)
+        o1, al1, i1, c1 = a.cache.decode(q, aux=True)
+        o2, al2, i2, c2 = f.cache.step(k_t, v_t, q, aux=True)
+        torch.cuda.synchronize()
+        for bi in range(w.B):
+            Kg[bi, :, int(cur[bi])] = k_t[bi]; Vg[bi, :, int(cur[bi])] = v_t[bi]
+        cur = cur + 1
+        assert a.cache.error_flags() == 0 and f.cache.error_flags() == 0
+        assert f.cache.seq_lens.cpu().tolist() == cur.tolist() == a.cache.seq_lens.cpu().tolist()
+        assert torch.equal(i1, i2) and torch.equal(c1, c2), f"selection differs at step {t}"
+        assert (al1 - al2).abs().max().item() <= 1e-6
+        assert ((o1.float() - o2.float()).abs() <= 2.0 ** -7 * o1.float().abs() + 1e-6).all(), f"output differs at step {t}"
+        assert torch.equal(a.cache.v_mean, f.cache.v_mean), "running mean differs"
+        for bi in range(w.B):
+            n = int(cur[bi])
+            assert torch.equal(a.cache.K[bi, :, :n], f.cache.K[bi, :, :n]) and torch.equal(a.cache.V[bi, :, :n], f.cache.V[bi, :, :n])
+            n8 = n & ~7
+            assert torch.equal(a.cache.Kt[bi, :, :, :n8], f.cache.Kt[bi, :, :, :n8])
+        grown = Hn.Built(w, f.cache, Kg, Vg, cur.clone(), None)
+        say(Hn.compare_decode(grown, q, flags=FL))
+    # all keys identical: every group score ties, the k lowest positions, alpha = k / S for every head
+    wt = W.Workload("g4_bucket_ties", 1, 4, 1, 128, 10000, 16, 50, "f16", seed=55)
+    t = Hn.build_cache(wt)
+    t.K_src[:] = t.K_src[:, :, :1]
+    t = Hn.Built(wt, DecodeCache(1, 4, 1, 10048, 128, 16, 50, wt.torch_dtype, flags=FL), t.K_src, t.V_src, t.seq_lens, None)
+    t.cache.append(t.K_src, t.V_src)
+    q = W.draw_queries(wt, t.K_src, t.seq_lens)[0]
+    out, alpha, idx, chan = t.cache.decode(q, aux=True)
+    assert torch.equal(idx.cpu(), torch.arange(50, dtype=torch.int32).expand(1, 4, 50))
+    assert torch.allclose(alpha.cpu(), torch.full((1, 4), 50 / 10000), atol=1e-6)
+    Hn.compare_decode(t, q, flags=FL)
 
 
 # ------------------------------------------------------------------ the one-launch decode step
