@@ -3,15 +3,15 @@
 // more than one span's keys.  Step 2's top-k is found exactly without any workgroup seeing the whole
 // sequence:
 //   bk_scores   (units x n_span) Step 1 on a span of span_len positions: approximate logits as integer
-//               keys in LDS, counted by their first 11-bit digit; the span's keys go to the workspace
-//               sorted by that digit (descending, as (key, position) pairs), together with the table
-//               A[d] = number of the span's keys whose first digit is >= d, the span's largest logit and
+//               keys in LDS, counted by an 11-bit bucket that is monotone in the key; the span's keys go to
+//               the workspace sorted by bucket (descending, as (key, position) pairs), together with the table
+//               A[d] = number of the span's keys whose bucket is >= d, the span's largest logit and
 //               its softmax denominator
-//   bk_select   (units x n_span) every workgroup sums the tables of its unit's spans and finds the digit
-//               d0 in which the k-th largest key of the whole sequence lies: all keys with a larger digit
-//               are selected, and of the few keys with digit d0 (contiguous in every span's sorted array)
+//   bk_select_gather  (units x n_span) every workgroup sums the tables of its unit's spans and finds the
+//               bucket d0 in which the k-th largest key of the whole sequence lies: all keys of a higher bucket
+//               are selected, and of the few keys of bucket d0 (contiguous in every span's sorted array)
 //               the best are: they are read by every workgroup of the unit and ranked exactly by
-//               (key descending, position ascending) with radix passes over the remaining 21 key bits and,
+//               (key descending, position ascending) with radix passes over the key bits and,
 //               only among identical keys, over the position.  Each workgroup then writes its own span's
 //               selected positions, ascending (into idx_out at its place in the unit's list), its share of
 //               alpha's numerator, gathers its own span's selected rows of K and V (Step 2b) and leaves one
@@ -19,7 +19,7 @@
 //   bk_combine  (one workgroup per unit) merges the spans' partials, alpha, blend, store
 // Every workgroup attends over the selected rows of its own span: the gather is balanced when the selected
 // positions are spread over the sequence, and takes as long as the busiest span when they are not.
-// The local window is part of it: its positions count as digit 2047, above every finite key.
+// The local window is part of it: its positions count as bucket 2047, above every key's.
 // The grouped-query rule runs on the same plan: gs_logits leaves every head's logit numerators and statistics in
 // the workspace, bk_group_scores turns the group score into keys and publishes the spans per KV unit, and
 // bk_select_gather<GROUP> / bk_combine run per query head on the KV unit's tables (alpha from the head's own logits).
@@ -47,15 +47,25 @@ __device__ __forceinline__ void map_span(int U, int n_span, int& u, int& s) {
   }
 }
 
-// The bucket of a key.  Ordinary keys (approximate logits): their first 11 bits.  Group-score keys are
-// log2 of a sum of probabilities, x <= 2, often down to -1000: their first 11 bits (sign, exponent, two mantissa
-// bits) tell 20-30 values apart and thousands of keys would share the threshold's bucket.  For them the bucket
-// comes from u = 4 - x >= 2 instead: 4 exponent bits and 7 mantissa bits of u (128 buckets per octave of u),
-// counted down so that a larger score has a larger digit.  Both maps are monotone in the key, which is all the
-// selection needs of a bucket (ranking inside the threshold bucket uses the whole key); 2047 stays free.
+// The bucket of a key: 11 bits that are monotone in the key (which is all the selection needs of a bucket: ranking
+// inside the threshold bucket uses the whole key) and tell the keys around the threshold apart as finely as
+// possible; 2047 stays free for the local window.  A key's own first 11 bits (sign, exponent, two mantissa bits)
+// leave a few percent of a sequence in one bucket.
+//  - Ordinary keys (approximate logit numerators): sign, 5 exponent bits (magnitudes 2^-8 .. 2^23; smaller ones share
+//    the bucket next to zero, larger ones the outermost) and 5 mantissa bits: 32 buckets per octave.
+//  - Group-score keys are log2 of a sum of probabilities, x <= 2, often down to -1000: the bucket comes from
+//    u = 4 - x >= 2: 4 exponent bits and 7 mantissa bits of u (128 buckets per octave of u), counted down so that
+//    a larger score has a larger digit.
 template <bool GROUP>
 __device__ __forceinline__ uint32_t bucket_digit(uint32_t key) {
-  if (!GROUP) return key >> 21;
+  if (!GROUP) {
+    const bool pos = (key & 0x80000000u) != 0;
+    const uint32_t bits = pos ? key & 0x7fffffffu : ~key & 0x7fffffffu;      // magnitude bits of the float
+    const int e = (int)(bits >> 23) - 119;
+    uint32_t low = e < 0 ? 0u : (e > 31 ? 1023u : ((uint32_t)e << 5) | ((bits >> 18) & 31u));
+    low = low > 1022u ? 1022u : low;
+    return pos ? 1024u + low : 1023u - low;
+  }
   const uint32_t bits = __float_as_uint(4.0f - key_to_float(key));   // u > 0 (or +inf): the bits order like u
   const int e = (int)(bits >> 23) - 128;
   uint32_t low = e < 0 ? 0u : (e > 15 ? 2046u : ((uint32_t)e << 7) | ((bits >> 16) & 127u));
@@ -200,7 +210,10 @@ __global__ __launch_bounds__(NT, 4) void bk_scores(const BucketArgs a) {
       tmax = fmaxf(tmax, acc[e]);
       kx[e] = float_to_key(acc[e]);
     }
-    hist_add_chunk(hist, kx, win.S_old - c * 8);          // the window's positions are counted below
+    uint32_t dg[8];                                        // hist_add_chunk counts by the first 11 bits of what it is given
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dg[e] = bucket_digit<false>(kx[e]) << 21;
+    hist_add_chunk(hist, dg, win.S_old - c * 8);          // the window's positions are counted below
     uint4* dst = reinterpret_cast<uint4*>(keys + (c * 8 - p0));
     dst[0] = make_uint4(kx[0], kx[1], kx[2], kx[3]);
     dst[1] = make_uint4(kx[4], kx[5], kx[6], kx[7]);
@@ -238,7 +251,7 @@ __global__ __launch_bounds__(NT, 4) void bk_scores(const BucketArgs a) {
     if (lane == 0) {
       const uint32_t key = float_to_key(dot);
       keys[S_fl + wave - p0] = key;
-      if (S_fl + wave < win.S_old) atomicAdd(&hist[hist_slot(key >> 21)], 1u);
+      if (S_fl + wave < win.S_old) atomicAdd(&hist[hist_slot(bucket_digit<false>(key))], 1u);
     }
   }
   // the part of the local window that lies in this span counts as the top digit
@@ -533,8 +546,8 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
     }
     __syncthreads();
   }
-  // a candidate as one number: the 21 key bits below the first digit (group-score keys: all 32), then the position
-  // counted down from the top, so that "larger" is "larger key, or equal key and lower position"; t = its span
+  // a candidate as one 52-bit number: the key, then the position counted down from the top, so that "larger" is
+  // "larger key, or equal key and lower position"; t = its span
   auto candidate = [&](int i, int& t) -> uint64_t {
     uint32_t key, pos;
     if (resident) {
@@ -545,20 +558,17 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
       key = a.skey_ws[(slot0 + t) * P + e];
       pos = a.spos_ws[(slot0 + t) * P + e];
     }
-    return ((uint64_t)(GROUP ? key : key & 0x1fffffu) << 20) | (uint64_t)(kPosMask - pos);
+    return ((uint64_t)key << 20) | (uint64_t)(kPosMask - pos);
   };
 
-  // ---- exact rank among the candidates: radix passes of 11, 10, 10 and 10 bits (group-score keys, whose bucket
-  // is not their first digit: the whole key, one more pass of 11 bits in front); stop as soon as the remaining bin
-  // is taken whole (with distinct keys: after the key bits) ----
+  // ---- exact rank among the candidates: radix passes of 11, 11, 10 (the key) and 10, 10 bits (the position); stop
+  // as soon as the remaining bin is taken whole (with distinct keys: after the key bits at the latest) ----
   uint64_t mask = 0, thr = 0;
   if (need < C0) {
     int in_bin = C0;
-    constexpr int kPasses = GROUP ? 5 : 4;
-    for (int pass = 0; pass < kPasses && need < in_bin; ++pass) {
-      const int lead = kPasses - 4;                // passes of 11 bits before the last three of 10
-      const int shift = pass <= lead ? 30 + 11 * (lead - pass) : 30 - 10 * (pass - lead);
-      const uint32_t dmask = pass <= lead ? 0x7ffu : 0x3ffu;
+    for (int pass = 0; pass < 5 && need < in_bin; ++pass) {
+      const int shift = pass < 2 ? 41 - 11 * pass : 40 - 10 * pass;
+      const uint32_t dmask = pass < 2 ? 0x7ffu : 0x3ffu;
       if (pass > 0) {
         for (int i = tid; i < kRadixBins; i += NT) hist[i] = 0u;
         __syncthreads();
@@ -600,7 +610,7 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
   auto mark = [&](int e, uint32_t key, uint32_t pos) {
     bool take = e < n_above;
     if (!take) {
-      const uint64_t c = ((uint64_t)(GROUP ? key : key & 0x1fffffu) << 20) | (uint64_t)(kPosMask - pos);
+      const uint64_t c = ((uint64_t)key << 20) | (uint64_t)(kPosMask - pos);
       take = (c & mask) >= thr;
     }
     if (take) {
