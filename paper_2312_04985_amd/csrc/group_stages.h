@@ -130,13 +130,15 @@ __device__ __forceinline__ void select_channels_group(const GroupQueryLds& Q, co
 }
 
 // Step 1b for G heads at once: like stream_channel_rows, every loaded 16-byte chunk feeds G accumulators.
-template <class T, int G, class Finish>
+// Thread tid of STRIDE owns chunks chunk_begin + tid + i * STRIDE (STRIDE < NT: the caller divides the channel
+// rows of a chunk among NT / STRIDE groups of threads).
+template <class T, int G, int STRIDE = NT, class Finish>
 __device__ __forceinline__ void stream_channel_rows_group(const char* Kt_head, size_t row_bytes, const int* chan,
                                                           const float* qs, int qs_stride, int r, int chunk_begin,
                                                           int chunk_end, int tid, Finish&& finish) {
   const int n_batches = (r + 7) >> 3;
   const int n_chunks = chunk_end - chunk_begin;
-  const int my_chunks = n_chunks > tid ? (n_chunks - tid + NT - 1) / NT : 0;
+  const int my_chunks = n_chunks > tid ? (n_chunks - tid + STRIDE - 1) / STRIDE : 0;
   const int items = my_chunks * n_batches;
   float acc[G][8];
 #pragma unroll
@@ -145,7 +147,7 @@ __device__ __forceinline__ void stream_channel_rows_group(const char* Kt_head, s
     for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
   int ic = 0, ib = 0, cc = 0, cb = 0;
   auto issue_next = [&](uint4 (&v)[8]) {
-    const uint32_t voff = (uint32_t)(chunk_begin + tid + ic * NT) * 16u;
+    const uint32_t voff = (uint32_t)(chunk_begin + tid + ic * STRIDE) * 16u;
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       const int ch = __builtin_amdgcn_readfirstlane(chan[ib * 8 + t]);
@@ -166,7 +168,7 @@ __device__ __forceinline__ void stream_channel_rows_group(const char* Kt_head, s
       }
     }
     if (++cb == n_batches) {
-      finish(chunk_begin + tid + cc * NT, acc);
+      finish(chunk_begin + tid + cc * STRIDE, acc);
 #pragma unroll
       for (int h = 0; h < G; ++h)
 #pragma unroll

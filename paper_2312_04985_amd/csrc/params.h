@@ -157,16 +157,17 @@ hipError_t launch_read_probe(const void* src, size_t n_bytes, void* sink, hipStr
 hipError_t launch_clear(void* workspace, int n_bytes, hipStream_t s);
 
 // A kernel that takes more than 64 KiB of dynamic LDS has to be allowed to, once per kernel and device
-// (not per launch: the call costs host time).  `lds` = the bytes the coming launch asks for.
+// (not per launch: the call costs host time).  `lds` = the bytes the coming launch asks for; `limit` = what the
+// kernel is allowed from then on (a kernel with static LDS arrays as well must stay below 160 KiB minus those).
 template <auto Kern>
-hipError_t allow_lds(size_t lds) {
+hipError_t allow_lds(size_t lds, int limit = 160 * 1024) {
   if (lds <= 64 * 1024) return hipSuccess;
   static unsigned long long allowed = 0;   // bit d: done on device d (benign race: the call is idempotent)
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev < 0 || dev >= 64 || !((allowed >> dev) & 1ull)) {
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kern), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kern), hipFuncAttributeMaxDynamicSharedMemorySize, limit);
     if (e != hipSuccess) return e;
     if (dev >= 0 && dev < 64) allowed |= 1ull << dev;
   }

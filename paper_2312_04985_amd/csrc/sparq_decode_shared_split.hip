@@ -28,6 +28,12 @@ __device__ __forceinline__ void map_kv(int Ukv, int n, int& ukv, int& s) {
   }
 }
 
+// Thread groups that share the chunks of a gs_logits span (see there): 4 or 2 when the span has at most NT / 4 or
+// NT / 2 chunks and there are that many batches of 8 channel rows, else 1.  Host and device agree through this.
+__host__ __device__ constexpr int logit_row_groups(int span1, int n_batches) {
+  return (span1 <= NT / 4 * 8 && n_batches >= 4) ? 4 : ((span1 <= NT / 2 * 8 && n_batches >= 2) ? 2 : 1);
+}
+
 template <class T, int DH, int G>
 __global__ __launch_bounds__(NT, 2) void gs_logits(const GsArgs a) {
   __shared__ int rankp[NT];
@@ -93,8 +99,7 @@ __global__ __launch_bounds__(NT, 2) void gs_logits(const GsArgs a) {
   float mt[G], zt[G];
 #pragma unroll
   for (int h = 0; h < G; ++h) { mt[h] = -INFINITY; zt[h] = 0.0f; }
-  stream_channel_rows_group<T, G>(Kt_head, row_bytes, chan, qs, DH, d.r, p0 >> 3, end > p0 ? end >> 3 : p0 >> 3, tid,
-                                  [&](int c, const float (&acc)[G][8]) {
+  auto finish = [&](int c, const float (&acc)[G][8]) {
 #pragma unroll
     for (int h = 0; h < G; ++h) {
       float4* dst = reinterpret_cast<float4*>(z_unit + (size_t)h * d.S_max + c * 8);
@@ -107,7 +112,60 @@ __global__ __launch_bounds__(NT, 2) void gs_logits(const GsArgs a) {
         else zt[h] += exp2f((v - mt[h]) * esc[h]);
       }
     }
-  });
+  };
+  const int c_begin = p0 >> 3, c_end = end > p0 ? end >> 3 : p0 >> 3;
+  const int nb = r8 >> 3;
+  const int F = logit_row_groups(a.span1, nb);
+  if (F > 1) {
+    // Fewer chunks than threads: F groups of NT / F threads share every chunk, each taking 1 / F of the batches of 8
+    // channel rows, so that a thread's loads are in flight together instead of going through the pipeline one
+    // batch after the other.  The groups' partial sums meet in LDS and the first group finishes the chunks.
+    extern __shared__ __align__(16) float pacc[];                 // [F][G][span1]
+    const int P = a.span1;
+    if (F == 4) {
+      const int part = tid >> 7, t = tid & (NT / 4 - 1);
+      const int b0 = part * nb / 4, b1 = (part + 1) * nb / 4;
+      stream_channel_rows_group<T, G, NT / 4>(Kt_head, row_bytes, chan + 8 * b0, qs + 8 * b0, DH, 8 * (b1 - b0), c_begin, c_end, t,
+                                              [&](int c, const float (&acc)[G][8]) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          float4* dst = reinterpret_cast<float4*>(pacc + (size_t)(part * G + h) * P + (c * 8 - p0));
+          dst[0] = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
+          dst[1] = make_float4(acc[h][4], acc[h][5], acc[h][6], acc[h][7]);
+        }
+      });
+    } else {
+      const int part = tid >> 8, t = tid & (NT / 2 - 1);
+      const int b0 = part * nb / 2, b1 = (part + 1) * nb / 2;
+      stream_channel_rows_group<T, G, NT / 2>(Kt_head, row_bytes, chan + 8 * b0, qs + 8 * b0, DH, 8 * (b1 - b0), c_begin, c_end, t,
+                                              [&](int c, const float (&acc)[G][8]) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          float4* dst = reinterpret_cast<float4*>(pacc + (size_t)(part * G + h) * P + (c * 8 - p0));
+          dst[0] = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
+          dst[1] = make_float4(acc[h][4], acc[h][5], acc[h][6], acc[h][7]);
+        }
+      });
+    }
+    __syncthreads();
+    for (int c = c_begin + tid; c < c_end; c += NT) {
+      float acc[G][8];
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] = 0.0f;
+        for (int part = 0; part < F; ++part) {                 // in the order of the channel list
+          const float4* src = reinterpret_cast<const float4*>(pacc + (size_t)(part * G + h) * P + (c * 8 - p0));
+          const float4 x0 = src[0], x1 = src[1];
+          acc[h][0] += x0.x; acc[h][1] += x0.y; acc[h][2] += x0.z; acc[h][3] += x0.w;
+          acc[h][4] += x1.x; acc[h][5] += x1.y; acc[h][6] += x1.z; acc[h][7] += x1.w;
+        }
+      }
+      finish(c, acc);
+    }
+  } else {
+    stream_channel_rows_group<T, G>(Kt_head, row_bytes, chan, qs, DH, d.r, c_begin, c_end, tid, finish);
+  }
   float tdot[G];
 #pragma unroll
   for (int h = 0; h < G; ++h) tdot[h] = wave < n_tail ? tail_row_dot<T>(tail, qs + h * DH, r8, lane) : 0.0f;
@@ -456,6 +514,17 @@ __global__ __launch_bounds__(NT, 2) void gs_gather(const GsArgs a) {
   }
 }
 
+// gs_logits with the dynamic LDS its thread groups' partial sums need (on top of ~9 KB of static arrays)
+template <class T, int DH, int G>
+hipError_t launch_logits(const GsArgs& a, hipStream_t s) {
+  const int F = logit_row_groups(a.span1, (a.d.r + 7) >> 3);
+  const size_t lds = F > 1 ? (size_t)F * G * a.span1 * sizeof(float) : 0;
+  hipError_t e = allow_lds<gs_logits<T, DH, G>>(lds + 16 * 1024, 128 * 1024);   // at most 64 KiB dynamic on top of the static arrays
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((gs_logits<T, DH, G>), dim3(a.d.B * a.d.H_kv * a.n1), dim3(NT), lds, s, a);
+  return hipGetLastError();
+}
+
 template <class T, int DH, int G>
 hipError_t launch_gs(const GsArgs& a, int dtype, hipStream_t s) {
   const int Ukv = a.d.B * a.d.H_kv;
@@ -463,8 +532,7 @@ hipError_t launch_gs(const GsArgs& a, int dtype, hipStream_t s) {
   hipError_t e;
   if ((e = allow_lds<gs_select<G>>(lds2)) != hipSuccess) return e;
   if ((e = allow_lds<gs_merge<G>>(lds3)) != hipSuccess) return e;
-  hipLaunchKernelGGL((gs_logits<T, DH, G>), dim3(Ukv * a.n1), dim3(NT), 0, s, a);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if ((e = launch_logits<T, DH, G>(a, s)) != hipSuccess) return e;
   hipLaunchKernelGGL(gs_select<G>, dim3(Ukv * a.n2), dim3(NT), lds2, s, a);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(gs_merge<G>, dim3(Ukv), dim3(NT), lds3, s, a);
@@ -498,13 +566,11 @@ size_t gs_merge_lds_bytes(int n2, int cand_cap) {
 namespace {
 template <class T, int DH>
 hipError_t launch_logits_dh(const GsArgs& a, hipStream_t s) {
-  const int Ukv = a.d.B * a.d.H_kv;
   switch (a.d.H / a.d.H_kv) {
-    case 2: hipLaunchKernelGGL((gs_logits<T, DH, 2>), dim3(Ukv * a.n1), dim3(NT), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((gs_logits<T, DH, 4>), dim3(Ukv * a.n1), dim3(NT), 0, s, a); break;
+    case 2: return launch_logits<T, DH, 2>(a, s);
+    case 4: return launch_logits<T, DH, 4>(a, s);
     default: return hipErrorInvalidValue;
   }
-  return hipGetLastError();
 }
 }  // namespace
 
