@@ -46,6 +46,7 @@ def parse():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-others", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--gqa-shared", action="store_true", help="the paper's grouped-query rule (one selection per KV head)")
     ap.add_argument("--stage-clocks", action="store_true",
                     help="profiling run on libsparq_clocks.so (python -m paper_2312_04985_amd.build --stage-clocks): prints the "
                          "per-stage time stamps of the step kernel's workgroups instead of the benchmark line")
@@ -140,7 +141,8 @@ def measure(name, K, Wm, args, full):
     seq0 = W.draw_seq_lens(w)                       # lengths seen by the first timed decode
     kps = W.k_per_seq(w, seq0)
     e = 2
-    step_bytes0 = T.sparq_decode_bytes(seq0.tolist(), w.H, w.d_h, w.r, w.k, e, None if kps is None else kps.tolist())
+    group_kv = w.H_kv if (args.gqa_shared and w.H != w.H_kv) else None     # bytes per KV head under the grouped-query rule
+    step_bytes0 = T.sparq_decode_bytes(seq0.tolist(), w.H, w.d_h, w.r, w.k, e, None if kps is None else kps.tolist(), group_kv)
     copies = args.copies or max(2, -(-(1 << 30) // step_bytes0["total"]))
     pre = max(0, CLOCK_WARMUP_STEPS - Wm)           # untimed extra steps so that the clocks have ramped up
     per_copy = -(-max(K, Wm, pre) // copies) + 1     # appends one copy receives in one pass
@@ -152,7 +154,8 @@ def measure(name, K, Wm, args, full):
     caches = []
     for _ in range(copies):
         c = DecodeCache(w.B, w.H, w.H_kv, S_max, w.d_h, w.r, w.k, w.torch_dtype, device=dev,
-                        flags=(B.SPARQ_FLAG_RAGGED_BATCH if w.ragged else 0) | layout_flag)
+                        flags=(B.SPARQ_FLAG_RAGGED_BATCH if w.ragged else 0) | layout_flag |
+                              (B.SPARQ_FLAG_GQA_SHARED if args.gqa_shared else 0))
         c.append(K_src, V_src, (seq0 - 1).to(dev))
         caches.append(c)
     torch.cuda.synchronize()
@@ -281,12 +284,12 @@ def measure(name, K, Wm, args, full):
     tot = {"stage1": 0, "stage3": 0, "blend": 0, "total": 0}
     kk = None if kps is None else kps.tolist()
     for i in range(K):
-        bts = T.sparq_decode_bytes((seq0 + (i // copies)).tolist(), w.H, w.d_h, w.r, w.k, e, kk)
+        bts = T.sparq_decode_bytes((seq0 + (i // copies)).tolist(), w.H, w.d_h, w.r, w.k, e, kk, group_kv)
         for key in tot:
             tot[key] += bts[key]
     dec_bytes = tot["total"] / K
     app_bytes = T.kv_append_bytes(w.B, w.H_kv, w.d_h, e)
-    dec_bytes0 = T.sparq_decode_bytes(seq0.tolist(), w.H, w.d_h, w.r, w.k, e, kk)["total"]
+    dec_bytes0 = T.sparq_decode_bytes(seq0.tolist(), w.H, w.d_h, w.r, w.k, e, kk, group_kv)["total"]
     achieved = (dec_bytes + app_bytes) / (step_avg_ms * 1e-3) / 1e9
     plan = B.sparq_decode_plan(caches[0].shape)
 
@@ -294,7 +297,8 @@ def measure(name, K, Wm, args, full):
         "workload": name, "ms_per_step": ms_per_step, "steps_per_s": 1e3 / ms_per_step, "plan": plan,
         "config": {"workload": name, "B": w.B, "H": w.H, "H_kv": w.H_kv, "d_h": w.d_h, "S": int(seq0.max()),
                    "r": w.r, "k": w.k if kps is None else "ceil(S_b/%d)" % w.k_div, "cache_dtype": w.dtype,
-                   "step": "sparq_decode_step (append + decode in one call)", "key_layout": args.layout, "cache_copies_rotated": copies,
+                   "step": "sparq_decode_step (append + decode in one call)", "key_layout": args.layout,
+                   "gqa_rule": "one selection per KV head (Section 4)" if group_kv else "every query head selects for itself", "cache_copies_rotated": copies,
                    "q_pool": n_pool, "S_max": S_max, "untimed_clock_warmup_steps": pre},
         "step_GBps": round((dec_bytes + app_bytes) / ms_per_step / 1e6, 1),
         "step_frac_of_peak": round((dec_bytes + app_bytes) / ms_per_step / 1e6 / HBM_PEAK_GBS, 4),
@@ -303,10 +307,10 @@ def measure(name, K, Wm, args, full):
                           "how": "one HIP event after every step of a separate pass of K steps"},
         "two_launch_step_ms": round(two_call_ms, 5), "decode_launch_ms": round(dec_avg_ms, 5),
         "decode_launch_GBps": round(dec_bytes0 / dec_avg_ms / 1e6, 1), "append_launch_ms": round(append_ms, 5),
-        "roofline": {"kernel": plan + (" with the append built in (sparq_decode_step)" if plan.startswith(("sparq_decode_fused", "bk_scores")) else
+        "roofline": {"kernel": plan + (" with the append built in (sparq_decode_step)" if plan.startswith("sparq_decode_fused") or "digit-bucket" in plan else
                                        "; sparq_decode_step runs append_one_row first"),
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic_from_profile(name),
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None if group_kv else traffic_from_profile(name),
                      "algorithmic_bytes_per_launch": int(dec_bytes + app_bytes), "avg_launch_ms": round(step_avg_ms, 5),
                      "stage_bytes": dict({k2: int(v / K) for k2, v in tot.items() if k2 != "total"}, append=app_bytes)},
     }
@@ -356,17 +360,18 @@ def measure(name, K, Wm, args, full):
         torch.cuda.synchronize()
         Kh = W.to_codes(c.key_rows()); Vh = W.to_codes(c.V); qh = W.to_codes(q_pool[0])
         seq_h = c.seq_lens.cpu().numpy(); kk_h = None if kps is None else kps.numpy()
+        oflags = B.SPARQ_FLAG_GQA_SHARED if args.gqa_shared else 0
         reps, spent = 0, 0.0
         while spent < args.cpu_seconds and reps < 50:
             tc = time.perf_counter()
-            ref = O.sparq_decode(Kh, Vh, qh, seq_h, r=w.r, k=w.k, dtype=w.dtype_code, k_per_seq=kk_h)
+            ref = O.sparq_decode(Kh, Vh, qh, seq_h, r=w.r, k=w.k, dtype=w.dtype_code, k_per_seq=kk_h, flags=oflags)
             spent += time.perf_counter() - tc; reps += 1
         got = got_t.float().cpu().numpy().astype(np.float64)
         n_bad, max_diff = output_violations(got, ref.y, w.dtype_code)
         same_sets = bool(np.array_equal(idx_t.cpu().numpy()[..., :ref.i2.shape[-1]], ref.i2))
         if n_bad and not same_sets:
             # a position inside the band that the index-set rule leaves open: judge the output on the GPU's own sets
-            ref = O.sparq_decode(Kh, Vh, qh, seq_h, r=w.r, k=w.k, dtype=w.dtype_code, k_per_seq=kk_h,
+            ref = O.sparq_decode(Kh, Vh, qh, seq_h, r=w.r, k=w.k, dtype=w.dtype_code, k_per_seq=kk_h, flags=oflags,
                                  given_i2=np.ascontiguousarray(idx_t.cpu().numpy()[..., :ref.i2.shape[-1]]))
             n_bad, max_diff = output_violations(got, ref.y, w.dtype_code)
         if n_bad:
@@ -434,6 +439,16 @@ def main():
                              "dense_us": round(r.get("dense_ms_per_step", float("nan")) * 1e3, 2),
                              "speedup_vs_dense": r.get("speedup_vs_dense"), "plan": r["plan"],
                              "algorithmic_bytes_per_launch": r["roofline"]["algorithmic_bytes_per_launch"]}
+        # config 3 once more under the paper's grouped-query rule (a quarter of the bytes: one selection per KV head)
+        import copy
+        ga = copy.copy(args); ga.gqa_shared = True
+        r = measure("c3_llama3_8b_gqa", min(K, 100), min(Wm, 10), ga, full=False)
+        others["c3_llama3_8b_gqa, grouped-query rule"] = {
+            "step_us": round(r["ms_per_step"] * 1e3, 2), "steps_per_s": round(r["steps_per_s"], 1),
+            "frac_of_peak": r["roofline"]["frac"], "step_us_median": r["step_us_stats"]["median"],
+            "decode_launch_us": round(r["decode_launch_ms"] * 1e3, 2), "dense_us": round(r.get("dense_ms_per_step", float("nan")) * 1e3, 2),
+            "speedup_vs_dense": r.get("speedup_vs_dense"), "plan": r["plan"],
+            "algorithmic_bytes_per_launch": r["roofline"]["algorithmic_bytes_per_launch"]}
         rec["other_workloads"] = others
     print(json.dumps(rec))
 

@@ -21,14 +21,16 @@ def sparq_elements(S: int, d_h: int, r: int, k: int) -> int:
 
 
 def sparq_decode_bytes(seq_lens: Iterable[int], H: int, d_h: int, r: int, k: int, e: int = 2,
-                       k_per_seq: Optional[Iterable[int]] = None) -> dict:
+                       k_per_seq: Optional[Iterable[int]] = None, group_kv_heads: Optional[int] = None) -> dict:
     """Algorithmic HBM bytes of ONE sparq_decode launch, per stage, counted per query head:
     stage 1 reads r channel rows of S_b elements plus q; stage 3 reads k_b rows of K and of V;
-    the blend reads the fp32 mean value vector and writes the output row."""
+    the blend reads the fp32 mean value vector and writes the output row.  Under the paper's grouped-query
+    rule (group_kv_heads = H_kv) the channel rows and the selected rows are read once per KV head."""
     seq = list(seq_lens)
     ks = list(k_per_seq) if k_per_seq is not None else [k] * len(seq)
-    s1 = sum(H * (r * S * e + d_h * e) for S in seq)
-    s3 = sum(H * (2 * min(kb, S) * d_h * e) for S, kb in zip(seq, ks))
+    Hr = H if group_kv_heads is None else group_kv_heads
+    s1 = sum(Hr * r * S * e + H * d_h * e for S in seq)
+    s3 = sum(Hr * (2 * min(kb, S) * d_h * e) for S, kb in zip(seq, ks))
     blend = len(seq) * H * (4 * d_h + d_h * e)
     return {"stage1": s1, "stage3": s3, "blend": blend, "total": s1 + s3 + blend}
 

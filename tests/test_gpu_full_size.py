@@ -40,6 +40,21 @@ def test_full_size_every_unit(name, q_scale):
     torch.cuda.empty_cache()
 
 
+def test_full_size_grouped_query_rule_every_unit():
+    """Config 3 under the paper's grouped-query rule (one selection per KV head), at planted and at scaled-down
+    queries: every unit against the oracle."""
+    w = C["c3_llama3_8b_gqa"]
+    FL = B.SPARQ_FLAG_GQA_SHARED
+    for q_scale in (1.0, 0.02):
+        b = Hn.build_cache(w, single_appends=2, poison=None, v_offset=q_scale != 1.0, flags=FL)
+        q = W.draw_queries(w, b.K_src, b.seq_lens, n=1, q_scale=q_scale)[0]
+        stats = Hn.compare_decode(b, q, flags=FL)
+        say(f"[full-size, grouped-query rule] q_scale={q_scale}", stats)
+        assert stats["units"] == w.B * w.H_kv          # one selection per KV head is compared
+        del b
+        torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("name,n_units,q_scale", [("c5_gemma_7b_ragged", 24, 1.0), ("c5_gemma_7b_ragged", 16, 0.02),
                                                   ("paper_table2", 32, 1.0)])
 def test_full_size_sampled(name, n_units, q_scale):
@@ -56,13 +71,13 @@ def test_full_size_sampled(name, n_units, q_scale):
     torch.cuda.empty_cache()
 
 
-def step_case(name):
+def step_case(name, extra_flags=0):
     """Cache filled up to the last row but one, and the rows the step appends."""
     w = C[name]
     seq = W.draw_seq_lens(w)                       # lengths AFTER the step
     K_src, V_src = W.draw_kv(w, "cuda", n_rows=int(seq.max()))
     S_max = W.round_up(int(seq.max()), 64)
-    flags = B.SPARQ_FLAG_RAGGED_BATCH if w.ragged else 0
+    flags = (B.SPARQ_FLAG_RAGGED_BATCH if w.ragged else 0) | extra_flags
     c = DecodeCache(w.B, w.H, w.H_kv, S_max, w.d_h, w.r, w.k, w.torch_dtype, flags=flags)
     c.append(K_src, V_src, (seq - 1).cuda())       # all but the last row of every sequence
     last = (seq - 1).to(torch.int64).cuda().view(w.B, 1, 1, 1).expand(w.B, w.H_kv, 1, w.d_h)
@@ -72,15 +87,17 @@ def step_case(name):
     return w, b, q, k_new, v_new, flags
 
 
-@pytest.mark.parametrize("name", ["c2_llama2_7b", "c4_large_batch"])
-def test_full_size_one_launch_step_every_unit(name):
-    """The launch the benchmark times: sparq_decode_step on the full batch, the new row landing at S_b - 1
-    of every sequence; every unit against the oracle on the grown cache, cache state included."""
-    w, b, q, k_new, v_new, flags = step_case(name)
+@pytest.mark.parametrize("name,extra_flags", [("c2_llama2_7b", 0), ("c4_large_batch", 0), ("c3_llama3_8b_gqa", 0),
+                                              ("c3_llama3_8b_gqa", B.SPARQ_FLAG_GQA_SHARED)])
+def test_full_size_one_launch_step_every_unit(name, extra_flags):
+    """The call the benchmark times: sparq_decode_step on the full batch, the new row landing at S_b - 1
+    of every sequence; every unit against the oracle on the grown cache, cache state included.  Config 3 runs
+    the digit-bucket plan, also under the paper's grouped-query rule."""
+    w, b, q, k_new, v_new, flags = step_case(name, extra_flags)
     say(f"[full-size step] {name}: seq_lens {b.seq_lens[:6].tolist()}")
     stats = Hn.compare_decode(b, q, flags=flags, step_rows=(k_new, v_new))
     say("   ", stats)
-    assert stats["units"] == w.B * w.H
+    assert stats["units"] == w.B * (w.H_kv if extra_flags & B.SPARQ_FLAG_GQA_SHARED else w.H)
     del b
     torch.cuda.empty_cache()
 
