@@ -51,8 +51,8 @@ class Workload:
         return 0 if self.dtype == "f16" else 1
 
 
-# The five workloads the benchmark contract names, plus the paper's own microbenchmark shape
-# (Table 2: batch 64, 32 heads, d_h = 128, S = 4096, r = 32, k = 128, N(0,1) tensors).
+# The five workloads the benchmark contract names, the paper's own microbenchmark shape
+# (Table 2: batch 64, 32 heads, d_h = 128, S = 4096, r = 32, k = 128, N(0,1) tensors), and one long-cache shape.
 CONFIGS = {
     "c1_single_head": Workload("c1_single_head", 1, 1, 1, 128, 1024, 16, 128, "f16", planted=(4, 4), seed=1),
     "c2_llama2_7b": Workload("c2_llama2_7b", 16, 32, 32, 128, 4096, 32, 512, "f16", planted=(8, 8), seed=2),
@@ -61,6 +61,9 @@ CONFIGS = {
     "c5_gemma_7b_ragged": Workload("c5_gemma_7b_ragged", 32, 16, 16, 256, 16384, 64, 2048, "bf16",
                                    planted=(1, 16), ragged=(1024, 16384), k_div=8, seed=5),
     "paper_table2": Workload("paper_table2", 64, 32, 32, 128, 4096, 32, 128, "f16", recipe="gaussian", seed=6),
+    # beyond the contract: many heads with caches longer than one workgroup's LDS holds (the two-level selection
+    # plan, whose launches give Step 1 and Step 2 separately to the profiler's counters)
+    "long_many_heads": Workload("long_many_heads", 16, 32, 32, 128, 40960, 32, 1024, "bf16", planted=(8, 8), seed=7),
 }
 
 

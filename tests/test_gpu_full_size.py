@@ -56,7 +56,7 @@ def test_full_size_grouped_query_rule_every_unit():
 
 
 @pytest.mark.parametrize("name,n_units,q_scale", [("c5_gemma_7b_ragged", 24, 1.0), ("c5_gemma_7b_ragged", 16, 0.02),
-                                                  ("paper_table2", 32, 1.0)])
+                                                  ("paper_table2", 32, 1.0), ("long_many_heads", 24, 1.0)])
 def test_full_size_sampled(name, n_units, q_scale):
     w = C[name]
     say(f"[full-size, sampled] {name}: B={w.B} H={w.H}/{w.H_kv} d_h={w.d_h} S={w.S} r={w.r} k={w.k} {w.dtype} ragged={w.ragged}")
