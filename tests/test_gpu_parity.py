@@ -289,6 +289,29 @@ def test_grouped_query_shared_step_and_ties():
     Hn.compare_decode(t, q, flags=B.SPARQ_FLAG_GQA_SHARED)
 
 
+def test_grouped_query_two_level_plan_step_window_and_ragged_k():
+    """The grouped-query rule with more than 128 query heads on few KV heads (two-level selection per KV head): the
+    one-call step, a local window, a per-sequence k, duplicated keys."""
+    w = W.Workload("g4_two_level_step", 9, 16, 4, 64, 16500, 16, 200, "f16", seed=56, k_div=120)
+    FL = B.SPARQ_FLAG_GQA_SHARED
+    seq = torch.tensor([16500 - 700 * i for i in range(w.B)], dtype=torch.int32)
+    b = Hn.build_cache(w, seq_lens=seq, S_max=16512, v_offset=True, dup_rows=300, flags=0)
+    b.cache.with_params(w.r, w.k, FL, local_window=16)
+    assert "several workgroups per KV head" in B.sparq_decode_plan(b.cache.shape)
+    q = W.draw_queries(w, b.K_src, b.seq_lens, q_scale=0.05)[0]
+    say(Hn.compare_decode(b, q, flags=FL, local_window=16))
+    kn, vn = W.draw_kv(W.scaled(w, seed=57), "cuda", n_rows=1, v_offset=True)
+    out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q, b.k_per_seq.cuda())
+    torch.cuda.synchronize()
+    assert b.cache.seq_lens.cpu().tolist() == (seq + 1).tolist() and b.cache.error_flags() == 0
+    Kg, Vg = torch.cat([b.K_src, kn], dim=2), torch.cat([b.V_src, vn], dim=2)
+    for i in range(w.B):
+        Kg[i, :, int(seq[i])] = kn[i, :, 0]; Vg[i, :, int(seq[i])] = vn[i, :, 0]
+    grown = Hn.Built(w, b.cache, Kg, Vg, b.seq_lens + 1, b.k_per_seq)
+    say(Hn.compare_decode(grown, q, flags=FL, local_window=16))
+    assert torch.equal(out.view(torch.int16), b.cache.decode(q, b.k_per_seq.cuda()).view(torch.int16))
+
+
 def test_grouped_query_rule_on_the_digit_bucket_plan_steps_and_ties():
     """The grouped-query rule for few heads with long caches (one digit-bucket selection per KV head): several
     one-call steps with ragged lengths, so that the new row lands in different places of a group of 8 positions and
@@ -621,8 +644,8 @@ def test_single_copy_step_and_refusals():
      dict(flags=B.SPARQ_FLAG_TAU_SQRT_R | B.SPARQ_FLAG_NO_REALLOC)),
 ])
 def test_long_sequence_plan(name, kw, extra):
-    """S_max beyond ~35 000 positions: spans select their own top-k, one workgroup merges the candidates.
-    Ragged: the second sequence ends inside the first span, so later spans of it are empty."""
+    """S_max beyond what one workgroup's LDS holds (~35 000 positions), few heads: the digit-bucket plan over
+    up to 64 spans.  Ragged: the second sequence ends inside the first span, so later spans of it are empty."""
     w = W.Workload(name, seed=95, **kw)
     seq = torch.tensor([w.S if i == 0 else 5000 + 3 * i for i in range(w.B)], dtype=torch.int32)
     st = run(w, q_scale=0.02, v_offset=True, seq_lens=seq, single_appends=3, **extra)
@@ -630,7 +653,7 @@ def test_long_sequence_plan(name, kw, extra):
 
 
 def test_long_sequence_step_ties_and_ragged_k():
-    """The one-call step under the long plan; duplicated keys at the threshold across span boundaries;
+    """The one-call step on a long cache with few heads; duplicated keys at the threshold across span boundaries;
     a per-sequence k."""
     w = W.Workload("long_step", 2, 2, 2, 128, 45000, 16, 256, "f16", seed=96, k_div=200)
     seq = torch.tensor([45000, 9000], dtype=torch.int32)
@@ -642,6 +665,45 @@ def test_long_sequence_step_ties_and_ragged_k():
     out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q, b.k_per_seq.cuda())
     torch.cuda.synchronize()
     assert b.cache.seq_lens.cpu().tolist() == [45001, 9001] and b.cache.error_flags() == 0
+    Kg, Vg = torch.cat([b.K_src, kn], dim=2), torch.cat([b.V_src, vn], dim=2)      # room for one more row
+    for i in range(w.B):                                                            # the row lands at S_b
+        Kg[i, :, int(seq[i])] = kn[i, :, 0]; Vg[i, :, int(seq[i])] = vn[i, :, 0]
+    grown = Hn.Built(w, b.cache, Kg, Vg, b.seq_lens + 1, b.k_per_seq)
+    say(Hn.compare_decode(grown, q))
+    assert torch.equal(out.view(torch.int16), b.cache.decode(q, b.k_per_seq.cuda()).view(torch.int16))
+
+
+@pytest.mark.parametrize("name,kw,extra", [
+    ("two_level_d64_window", dict(B=5, H=32, H_kv=32, d_h=64, S=36001, r=8, k=100, dtype="f16"), dict(local_window=24)),
+    ("two_level_gqa_large_k", dict(B=3, H=48, H_kv=12, d_h=128, S=40000, r=16, k=6000, dtype="bf16"), {}),
+    ("two_level_tau_sqrt_dh", dict(B=9, H=16, H_kv=16, d_h=128, S=35500, r=16, k=300, dtype="f16"),
+     dict(flags=B.SPARQ_FLAG_TAU_SQRT_DH)),
+])
+def test_two_level_plan_many_heads(name, kw, extra):
+    """More than 128 (sequence, head) units beyond one workgroup's LDS: every span selects its own top-k, one
+    workgroup per unit merges the candidates (the two-level selection plan).  Ragged lengths: later spans of the
+    shorter sequences are empty or partial."""
+    w = W.Workload(name, seed=98, **kw)
+    assert "two-level" in B.sparq_decode_plan(B.make_shape(w.B, w.H, w.H_kv, W.round_up(w.S, 64), w.d_h, w.r, w.k, w.dtype_code))
+    seq = torch.tensor([w.S if i == 0 else 9000 + 4001 * i for i in range(w.B)], dtype=torch.int32)
+    st = run(w, q_scale=0.02, v_offset=True, seq_lens=seq, single_appends=2, **extra)
+    say(st)
+
+
+def test_two_level_plan_many_heads_step_ties_and_ragged_k():
+    """The one-call step under the two-level plan (append kernel, then the plan's launches); duplicated keys at the
+    threshold across span boundaries; a per-sequence k."""
+    w = W.Workload("two_level_step", 5, 32, 32, 64, 37000, 8, 256, "f16", seed=99, k_div=150)
+    seq = torch.tensor([37000, 9000, 20000, 36001, 64], dtype=torch.int32)
+    b = Hn.build_cache(w, v_offset=True, seq_lens=seq, S_max=37056, dup_rows=400)
+    assert "two-level" in B.sparq_decode_plan(b.cache.shape)
+    b = Hn.Built(w, b.cache, b.K_src, b.V_src, b.seq_lens, W.k_per_seq(w, seq))
+    q = W.draw_queries(w, b.K_src, b.seq_lens, q_scale=0.02)[0]
+    say(Hn.compare_decode(b, q))
+    kn, vn = W.draw_kv(W.scaled(w, seed=100), "cuda", n_rows=1, v_offset=True)
+    out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q, b.k_per_seq.cuda())
+    torch.cuda.synchronize()
+    assert b.cache.seq_lens.cpu().tolist() == (seq + 1).tolist() and b.cache.error_flags() == 0
     Kg, Vg = torch.cat([b.K_src, kn], dim=2), torch.cat([b.V_src, vn], dim=2)      # room for one more row
     for i in range(w.B):                                                            # the row lands at S_b
         Kg[i, :, int(seq[i])] = kn[i, :, 0]; Vg[i, :, int(seq[i])] = vn[i, :, 0]
