@@ -268,6 +268,10 @@ def measure(name, K, Wm, args, full):
     restore()
     per = per_step_events(fused_step, K)
 
+    # the decode call alone at the lengths the timed steps ended with (not a multiple of 8 or of 4096: the newest
+    # rows come from K, and a few chunks start another round of the stream), so that step minus this is the append
+    dec_same_ms = timed_events(lambda i: check(lib.sparq_decode(*table[i % copies][par[i % copies]][i % n_pool]["decode"])), K)
+
     # for the record: the step as two calls, the decode call alone, the append call alone
     restore()
     two_call_ms = timed(two_call_step, K)
@@ -306,6 +310,7 @@ def measure(name, K, Wm, args, full):
                           "standard_error": round(float(per.std(ddof=1) / np.sqrt(len(per))) * 1e3, 3), "n": int(len(per)),
                           "how": "one HIP event after every step of a separate pass of K steps"},
         "two_launch_step_ms": round(two_call_ms, 5), "decode_launch_ms": round(dec_avg_ms, 5),
+        "decode_launch_at_step_lengths_ms": round(dec_same_ms, 5),
         "decode_launch_GBps": round(dec_bytes0 / dec_avg_ms / 1e6, 1), "append_launch_ms": round(append_ms, 5),
         "roofline": {"kernel": plan + (" with the append built in (sparq_decode_step)" if plan.startswith("sparq_decode_fused") or "digit-bucket" in plan else
                                        "; sparq_decode_step runs append_one_row first"),
@@ -422,7 +427,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
     }
-    for key in ("config", "step_GBps", "step_frac_of_peak", "step_us_stats", "two_launch_step_ms", "decode_launch_ms",
+    for key in ("config", "step_GBps", "step_frac_of_peak", "step_us_stats", "two_launch_step_ms", "decode_launch_ms", "decode_launch_at_step_lengths_ms",
                 "decode_launch_GBps", "append_launch_ms", "hbm_probe", "roofline", "cpu_baseline", "dense_ms_per_step",
                 "dense_GBps", "dense_frac_of_peak", "speedup_vs_dense", "transfer_ratio_dense_over_sparq"):
         if key in main_rec:
