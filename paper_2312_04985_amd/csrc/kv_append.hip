@@ -323,7 +323,7 @@ __global__ __launch_bounds__(256) void copy_probe(uint4* dst, const uint4* src, 
   for (; i + 7 * T < end; i += 8 * T) {
     uint4 v[8];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) v[t] = src[i + t * T];
+    for (int t = 0; t < 8; ++t) v[t] = load16(src + i + t * T);
 #pragma unroll
     for (int t = 0; t < 8; ++t) dst[i + t * T] = v[t];
   }
@@ -344,14 +344,14 @@ __global__ __launch_bounds__(256) void read_probe(const uint4* src, size_t n16, 
   if (i + 7 * T < end) {
     uint4 va[8], vb[8];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) va[t] = src[i + t * T];
+    for (int t = 0; t < 8; ++t) va[t] = load16(src + i + t * T);
     i += 8 * T;
     for (; i + 15 * T < end; i += 16 * T) {
 #pragma unroll
-      for (int t = 0; t < 8; ++t) vb[t] = src[i + t * T];
+      for (int t = 0; t < 8; ++t) vb[t] = load16(src + i + t * T);
       fold(va);
 #pragma unroll
-      for (int t = 0; t < 8; ++t) va[t] = src[i + (8 + t) * T];
+      for (int t = 0; t < 8; ++t) va[t] = load16(src + i + (8 + t) * T);
       fold(vb);
     }
     fold(va);
