@@ -111,6 +111,16 @@ typedef struct {
    * recent positions are selected unconditionally and the other k_b - l are the best-scoring of the
    * older positions; alpha sums s-hat over the whole set.  0 = the plain top-k rule. */
   int32_t local_window;
+  /* 0, or the caller's bound on the lengths for this call: a multiple of 64, <= S_max, with seq_lens[b] <=
+   * S_bound for every sequence (for sparq_decode_step: after its append).  K, Kt and V keep the strides of
+   * S_max; the kernels, their LDS and the workspace are chosen for S_bound instead, which matters when the
+   * buffers are allocated for a far longer context than the batch has reached (one workgroup per head holds a
+   * 4-byte key per position up to the bound in LDS: buffers for 32 768 positions used at 8 192 decode 30 % slower
+   * when sized by S_max).  The bound is treated exactly as S_max is treated without it: a longer sequence is
+   * served over its first S_bound positions and reported (SPARQ_ERR_BAD_SEQ_LEN; its stored length is carried over
+   * unchanged), a step whose append would pass the bound leaves that sequence as it is (SPARQ_ERR_APPEND_FULL).  sparq_kv_append ignores the bound.  sparq_workspace_bytes depends on it: size the
+   * workspace for every bound that will be used (the calls check). */
+  int32_t S_bound;
 } sparq_shape;
 
 typedef struct {

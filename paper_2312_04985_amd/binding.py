@@ -30,7 +30,7 @@ class SparqShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("H_kv", ctypes.c_int32),
                 ("S_max", ctypes.c_int32), ("d_h", ctypes.c_int32), ("r", ctypes.c_int32),
                 ("k", ctypes.c_int32), ("dtype", ctypes.c_int32), ("flags", ctypes.c_uint32),
-                ("local_window", ctypes.c_int32)]
+                ("local_window", ctypes.c_int32), ("S_bound", ctypes.c_int32)]
 
 
 class SparqCache(ctypes.Structure):
@@ -117,9 +117,9 @@ def _stream(stream) -> int:
     return s.cuda_stream
 
 
-def make_shape(B, H, H_kv, S_max, d_h, r, k, dtype, flags=0, local_window=0) -> SparqShape:
+def make_shape(B, H, H_kv, S_max, d_h, r, k, dtype, flags=0, local_window=0, S_bound=0) -> SparqShape:
     code = {torch.float16: SPARQ_F16, torch.bfloat16: SPARQ_BF16}.get(dtype, dtype)
-    return SparqShape(B, H, H_kv, S_max, d_h, r, k, int(code), flags, local_window)
+    return SparqShape(B, H, H_kv, S_max, d_h, r, k, int(code), flags, local_window, S_bound)
 
 
 def make_cache(K, Kt, V, v_mean, seq_lens) -> SparqCache:

@@ -40,15 +40,20 @@ class DecodeCache:
         self._v_mean_alt = None      # second (v_mean, seq_lens) pair for the one-launch step, made on first use
         self._seq_lens_alt = None
 
-    def with_params(self, r: int, k: int, flags: int = 0, local_window: int = 0):
-        """The same buffers seen through another (r, k, flags, local window) setting."""
+    def with_params(self, r: int, k: int, flags: int = 0, local_window: int = 0, S_bound: int = 0):
+        """The same buffers seen through another (r, k, flags, local window, bound on the lengths) setting."""
         self.r, self.k = r, k
-        self.shape = B.make_shape(self.B, self.H, self.H_kv, self.S_max, self.d_h, r, k, self.dtype, flags, local_window)
+        self.shape = B.make_shape(self.B, self.H, self.H_kv, self.S_max, self.d_h, r, k, self.dtype, flags, local_window, S_bound)
         need = B.sparq_workspace_bytes(self.shape)          # the plan, and with it the scratch size, may change
         if need > self.workspace.numel():
             self.workspace = torch.zeros((need,), dtype=torch.uint8, device=self.device)
             B.sparq_workspace_init(self.workspace)
         return self
+
+    def with_bound(self, S_bound: int):
+        """Promise that no sequence is (or, in a step, becomes) longer than S_bound, a multiple of 64 (0: S_max): kernels
+        and workspace are then chosen for that length instead of the buffers' S_max."""
+        return self.with_params(self.r, self.k, self.shape.flags, self.shape.local_window, S_bound)
 
     def append(self, k_new: torch.Tensor, v_new: torch.Tensor, n_new_per_seq: Optional[torch.Tensor] = None, stream=None):
         """k_new, v_new: [B, H_kv, n_new, d_h] (or [B, H_kv, d_h] for one row)."""

@@ -25,6 +25,7 @@ int check_shape(const sparq_shape* s) {
   if ((s->flags & SPARQ_FLAG_SINGLE_K) && (s->flags & SPARQ_FLAG_TILED_K)) return SPARQ_EINVAL;
   if ((s->flags & SPARQ_FLAG_TAU_SQRT_DH) && (s->flags & SPARQ_FLAG_TAU_SQRT_R)) return SPARQ_EINVAL;
   if (s->local_window < 0) return SPARQ_EINVAL;
+  if (s->S_bound < 0 || s->S_bound > s->S_max || s->S_bound % 64 != 0) return SPARQ_EINVAL;
   if (s->d_h != 64 && s->d_h != 128 && s->d_h != 256) return SPARQ_EUNSUPPORTED;
   // element offsets inside one tensor are formed in size_t; the counts themselves stay in int32
   if ((int64_t)s->B * s->H > (int64_t)1 << 30) return SPARQ_EUNSUPPORTED;
@@ -50,6 +51,15 @@ void dense_plan(const sparq_shape* s, int* n_split, int* rows_per_split) {
   rows = (rows + 63) / 64 * 64;
   *rows_per_split = rows;
   *n_split = (s->S_max + rows - 1) / rows;
+}
+
+// The shape that plans, LDS and workspace are sized for: the caller's bound on the lengths (S_bound), where one is
+// given, stands in for S_max; the buffers keep the strides of the shape's own S_max.
+sparq_shape bounded(const sparq_shape* s) {
+  sparq_shape e = *s;
+  if (s->S_bound > 0) e.S_max = s->S_bound;
+  e.S_bound = 0;
+  return e;
 }
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -310,7 +320,7 @@ hipError_t enqueue_decode(const sparq_shape* shape, const DecodeArgs& a, void* w
     ap.K = a.K; ap.Kt = one_k ? nullptr : a.Kt; ap.V = a.V; ap.v_mean = const_cast<float*>(a.v_mean); ap.seq_lens = const_cast<int32_t*>(a.seq_lens);
     ap.v_mean_out = a.v_mean_next; ap.seq_lens_out = a.seq_lens_next;
     ap.k_new = a.k_new; ap.v_new = a.v_new; ap.n_new_per_seq = nullptr; ap.err = a.err;
-    ap.B = a.B; ap.H_kv = a.H_kv; ap.S_max = a.S_max; ap.d_h = a.d_h; ap.n_new = 1; ap.tiled = tiled_k(shape) ? 1 : 0;
+    ap.B = a.B; ap.H_kv = a.H_kv; ap.S_max = a.S_max; ap.S_stride = a.S_stride; ap.d_h = a.d_h; ap.n_new = 1; ap.tiled = tiled_k(shape) ? 1 : 0;
     hipError_t e = launch_append(ap, shape->dtype, s);
     if (e != hipSuccess) return e;
     d.v_mean = a.v_mean_next; d.seq_lens = a.seq_lens_next;
@@ -415,10 +425,12 @@ void* static_scratch(hipStream_t s) {
 
 extern "C" {
 
-int sparq_workspace_bytes(const sparq_shape* shape, size_t* out_bytes) {
-  int rc = check_shape(shape);
+int sparq_workspace_bytes(const sparq_shape* caller_shape, size_t* out_bytes) {
+  int rc = check_shape(caller_shape);
   if (rc != SPARQ_OK) return rc;
   if (!out_bytes) return SPARQ_EINVAL;
+  const sparq_shape sized = bounded(caller_shape);
+  const sparq_shape* shape = &sized;
   *out_bytes = workspace_need(shape);
   return SPARQ_OK;
 }
@@ -428,30 +440,35 @@ int sparq_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stre
   return launch_clear(workspace, kControlBytes, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
-int sparq_kv_append(const sparq_shape* shape, const sparq_cache* cache, const void* k_new,
+int sparq_kv_append(const sparq_shape* caller_shape, const sparq_cache* cache, const void* k_new,
                     const void* v_new, int32_t n_new, const int32_t* n_new_per_seq,
                     void* workspace, size_t workspace_bytes, void* hip_stream) {
-  int rc = check_shape(shape);
-  if (rc == SPARQ_OK) rc = check_cache(cache, shape);
+  int rc = check_shape(caller_shape);
+  if (rc == SPARQ_OK) rc = check_cache(cache, caller_shape);
   if (rc != SPARQ_OK) return rc;
-  if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new) || n_new < 1 || n_new > shape->S_max) return SPARQ_EINVAL;
+  const sparq_shape sized = bounded(caller_shape);
+  const sparq_shape* shape = &sized;
+  if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new) || n_new < 1 || n_new > caller_shape->S_max) return SPARQ_EINVAL;
   rc = check_workspace(shape, workspace, workspace_bytes);
   if (rc != SPARQ_OK) return rc;
   AppendArgs a;
   a.K = cache->K; a.Kt = single_k(shape) ? nullptr : cache->Kt; a.V = cache->V; a.v_mean = cache->v_mean; a.seq_lens = cache->seq_lens;
   a.v_mean_out = cache->v_mean; a.seq_lens_out = cache->seq_lens;
   a.k_new = k_new; a.v_new = v_new; a.n_new_per_seq = n_new_per_seq; a.err = static_cast<int32_t*>(workspace);
-  a.B = shape->B; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h; a.n_new = n_new; a.tiled = tiled_k(shape) ? 1 : 0;
+  a.B = shape->B; a.H_kv = shape->H_kv; a.S_max = a.S_stride = caller_shape->S_max;   // S_bound does not limit an append
+  a.d_h = shape->d_h; a.n_new = n_new; a.tiled = tiled_k(shape) ? 1 : 0;
   return launch_append(a, shape->dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
-int sparq_decode(const sparq_shape* shape, const sparq_cache* cache, const void* q,
+int sparq_decode(const sparq_shape* caller_shape, const sparq_cache* cache, const void* q,
                  const int32_t* k_per_seq, void* out, float* alpha_out, int32_t* idx_out,
                  int32_t idx_stride, int32_t* chan_out, void* workspace, size_t workspace_bytes,
                  void* hip_stream) {
-  int rc = check_shape(shape);
-  if (rc == SPARQ_OK) rc = check_cache(cache, shape);
+  int rc = check_shape(caller_shape);
+  if (rc == SPARQ_OK) rc = check_cache(cache, caller_shape);
   if (rc != SPARQ_OK) return rc;
+  const sparq_shape sized = bounded(caller_shape);
+  const sparq_shape* shape = &sized;
   if (!q || !out || !aligned16(q) || !aligned16(out)) return SPARQ_EINVAL;
   if (idx_out && idx_stride < 1) return SPARQ_EINVAL;
   rc = check_workspace(shape, workspace, workspace_bytes);
@@ -462,18 +479,20 @@ int sparq_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
   a.q = q; a.k_per_seq = k_per_seq; a.out = out; a.alpha_out = alpha_out; a.idx_out = idx_out;
   a.k_new = nullptr; a.v_new = nullptr; a.v_mean_next = nullptr; a.seq_lens_next = nullptr;
   a.chan_out = chan_out; a.err = static_cast<int32_t*>(workspace);
-  a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h;
+  a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.S_stride = caller_shape->S_max; a.d_h = shape->d_h;
   a.r = shape->r; a.k = shape->k; a.idx_stride = idx_out ? idx_stride : 0; a.flags = shape->flags;
   a.local_window = shape->local_window;
   return enqueue_decode(shape, a, workspace, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
-int sparq_decode_noalloc(const sparq_shape* shape, const sparq_cache* cache, const void* q,
+int sparq_decode_noalloc(const sparq_shape* caller_shape, const sparq_cache* cache, const void* q,
                          const int32_t* k_per_seq, void* out, float* alpha_out, int32_t* idx_out,
                          int32_t idx_stride, int32_t* chan_out, int32_t* error_word, void* hip_stream) {
-  int rc = check_shape(shape);
-  if (rc == SPARQ_OK) rc = check_cache(cache, shape);
+  int rc = check_shape(caller_shape);
+  if (rc == SPARQ_OK) rc = check_cache(cache, caller_shape);
   if (rc != SPARQ_OK) return rc;
+  const sparq_shape sized = bounded(caller_shape);
+  const sparq_shape* shape = &sized;
   if (!q || !out || !aligned16(q) || !aligned16(out)) return SPARQ_EINVAL;
   if (idx_out && idx_stride < 1) return SPARQ_EINVAL;
   if (!decode_supported(shape)) return SPARQ_EUNSUPPORTED;
@@ -486,20 +505,22 @@ int sparq_decode_noalloc(const sparq_shape* shape, const sparq_cache* cache, con
   a.q = q; a.k_per_seq = k_per_seq; a.out = out; a.alpha_out = alpha_out; a.idx_out = idx_out;
   a.k_new = nullptr; a.v_new = nullptr; a.v_mean_next = nullptr; a.seq_lens_next = nullptr;
   a.chan_out = chan_out; a.err = error_word ? error_word : static_cast<int32_t*>(ws);
-  a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h;
+  a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.S_stride = caller_shape->S_max; a.d_h = shape->d_h;
   a.r = shape->r; a.k = shape->k; a.idx_stride = idx_out ? idx_stride : 0; a.flags = shape->flags;
   a.local_window = shape->local_window;
   return enqueue_decode(shape, a, ws, s) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
-int sparq_decode_step(const sparq_shape* shape, const sparq_cache* cache, const void* k_new,
+int sparq_decode_step(const sparq_shape* caller_shape, const sparq_cache* cache, const void* k_new,
                       const void* v_new, float* v_mean_next, int32_t* seq_lens_next, const void* q,
                       const int32_t* k_per_seq, void* out, float* alpha_out, int32_t* idx_out,
                       int32_t idx_stride, int32_t* chan_out, void* workspace, size_t workspace_bytes,
                       void* hip_stream) {
-  int rc = check_shape(shape);
-  if (rc == SPARQ_OK) rc = check_cache(cache, shape);
+  int rc = check_shape(caller_shape);
+  if (rc == SPARQ_OK) rc = check_cache(cache, caller_shape);
   if (rc != SPARQ_OK) return rc;
+  const sparq_shape sized = bounded(caller_shape);
+  const sparq_shape* shape = &sized;
   if (!q || !out || !aligned16(q) || !aligned16(out)) return SPARQ_EINVAL;
   if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)) return SPARQ_EINVAL;
   if (!v_mean_next || !seq_lens_next || !aligned16(v_mean_next)) return SPARQ_EINVAL;
@@ -513,17 +534,19 @@ int sparq_decode_step(const sparq_shape* shape, const sparq_cache* cache, const 
   a.q = q; a.k_per_seq = k_per_seq; a.out = out; a.alpha_out = alpha_out; a.idx_out = idx_out;
   a.k_new = k_new; a.v_new = v_new; a.v_mean_next = v_mean_next; a.seq_lens_next = seq_lens_next;
   a.chan_out = chan_out; a.err = static_cast<int32_t*>(workspace);
-  a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h;
+  a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.S_stride = caller_shape->S_max; a.d_h = shape->d_h;
   a.r = shape->r; a.k = shape->k; a.idx_stride = idx_out ? idx_stride : 0; a.flags = shape->flags;
   a.local_window = shape->local_window;
   return enqueue_decode(shape, a, workspace, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
-int dense_decode(const sparq_shape* shape, const sparq_cache* cache, const void* q, void* out,
+int dense_decode(const sparq_shape* caller_shape, const sparq_cache* cache, const void* q, void* out,
                  void* workspace, size_t workspace_bytes, void* hip_stream) {
-  int rc = check_shape(shape);
-  if (rc == SPARQ_OK) rc = check_cache(cache, shape);
+  int rc = check_shape(caller_shape);
+  if (rc == SPARQ_OK) rc = check_cache(cache, caller_shape);
   if (rc != SPARQ_OK) return rc;
+  const sparq_shape sized = bounded(caller_shape);
+  const sparq_shape* shape = &sized;
   if (!q || !out || !aligned16(q) || !aligned16(out)) return SPARQ_EINVAL;
   rc = check_workspace(shape, workspace, workspace_bytes);
   if (rc != SPARQ_OK) return rc;
@@ -532,7 +555,7 @@ int dense_decode(const sparq_shape* shape, const sparq_cache* cache, const void*
   a.K = cache->K; a.V = cache->V; a.seq_lens = cache->seq_lens; a.q = q; a.out = out;
   a.partials = reinterpret_cast<float*>(static_cast<char*>(workspace) + kControlBytes);
   a.err = static_cast<int32_t*>(workspace);
-  a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.d_h = shape->d_h;
+  a.B = shape->B; a.H = shape->H; a.H_kv = shape->H_kv; a.S_max = shape->S_max; a.S_stride = caller_shape->S_max; a.d_h = shape->d_h;
   dense_plan(shape, &a.n_split, &a.rows_per_split);
   return launch_dense(a, shape->dtype, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
@@ -556,8 +579,10 @@ int sparq_read_probe(const void* src, size_t n_bytes, void* sink, size_t sink_by
   return launch_read_probe(src, n_bytes, sink, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? SPARQ_OK : SPARQ_ELAUNCH;
 }
 
-const char* sparq_decode_plan(const sparq_shape* shape) {
-  if (check_shape(shape) != SPARQ_OK) return "invalid shape";
+const char* sparq_decode_plan(const sparq_shape* caller_shape) {
+  if (check_shape(caller_shape) != SPARQ_OK) return "invalid shape";
+  const sparq_shape sized = bounded(caller_shape);
+  const sparq_shape* shape = &sized;
   switch (choose_plan(shape).plan) {
     case kPlanFused: return "sparq_decode_fused (one workgroup per head, one launch)";
     case kPlanLong: return "long_scores + long_merge + split_gather + split_combine (two-level selection plan)";
@@ -570,11 +595,13 @@ const char* sparq_decode_plan(const sparq_shape* shape) {
   }
 }
 
-int sparq_stage_clocks(const sparq_shape* shape, size_t* offset_bytes, int32_t* n_workgroups, int32_t* stamps_per_workgroup) {
+int sparq_stage_clocks(const sparq_shape* caller_shape, size_t* offset_bytes, int32_t* n_workgroups, int32_t* stamps_per_workgroup) {
   if (!offset_bytes || !n_workgroups || !stamps_per_workgroup) return SPARQ_EINVAL;
-  const int rc = check_shape(shape);
+  const int rc = check_shape(caller_shape);
   if (rc != SPARQ_OK) return rc;
 #ifdef SPARQ_STAGE_CLOCKS
+  const sparq_shape sized = bounded(caller_shape);
+  const sparq_shape* shape = &sized;
   if (choose_plan(shape).plan != kPlanFused) return SPARQ_EUNSUPPORTED;
   *offset_bytes = kControlBytes; *n_workgroups = shape->B * shape->H; *stamps_per_workgroup = kStageStamps;
   return SPARQ_OK;

@@ -294,7 +294,7 @@ __device__ __forceinline__ uint4 gather_key_columns(const uint16_t* K_head, int 
   return make_uint4(w[0], w[1], w[2], w[3]);
 }
 // ... written as columns S-8 .. S-1 of Kt: one 16-byte store
-__device__ __forceinline__ void flush_key_columns(uint16_t* Kt_head, const uint16_t* K_head, int S_max, int d_h,
+__device__ __forceinline__ void flush_key_columns(uint16_t* Kt_head, const uint16_t* K_head, int S_stride, int d_h,
                                                   int S, int j, uint16_t newest) {
   // (a non-temporal store: each of these 16 bytes is a line of its own that nothing reads for the next 8 steps; with
   // 2048 KV heads the step is 1-2 % faster, with 512 it is 0.5 % slower)
@@ -302,7 +302,7 @@ __device__ __forceinline__ void flush_key_columns(uint16_t* Kt_head, const uint1
   const uint4 c = gather_key_columns(K_head, d_h, S, j, newest);
   u32x4 v;
   v.x = c.x; v.y = c.y; v.z = c.z; v.w = c.w;
-  __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(Kt_head + (size_t)j * S_max + (S - 8)));
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(Kt_head + (size_t)j * S_stride + (S - 8)));
 }
 
 // ------------------------------------------------------------------------------------------------

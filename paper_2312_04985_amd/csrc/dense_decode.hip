@@ -30,8 +30,8 @@ __global__ __launch_bounds__(DT) void dense_partial(const DenseArgs a) {
 
   const int sub = lane % LPR, slot = wave * RPW + lane / LPR;
   const size_t kv_head = (size_t)b * a.H_kv + hk;
-  const char* K_head = reinterpret_cast<const char*>(a.K) + kv_head * a.S_max * (size_t)(DH * 2) + sub * 16;
-  const char* V_head = reinterpret_cast<const char*>(a.V) + kv_head * a.S_max * (size_t)(DH * 2) + sub * 16;
+  const char* K_head = reinterpret_cast<const char*>(a.K) + kv_head * a.S_stride * (size_t)(DH * 2) + sub * 16;
+  const char* V_head = reinterpret_cast<const char*>(a.V) + kv_head * a.S_stride * (size_t)(DH * 2) + sub * 16;
   const uint16_t* qp = reinterpret_cast<const uint16_t*>(a.q) + ((size_t)b * a.H + h0) * DH + sub * 8;
   const float qscale = kLog2e / sqrtf((float)DH);
   float q8[G][8], acc[G][8], m_run[G], l_run[G];

@@ -36,8 +36,8 @@ __global__ __launch_bounds__(512) void append_one_row(const AppendArgs a) {
     const size_t head = (size_t)b * a.H_kv + hk;
     const uint4 kc = load16(reinterpret_cast<const uint16_t*>(a.k_new) + head * a.d_h + j0);
     const uint4 vc = load16(reinterpret_cast<const uint16_t*>(a.v_new) + head * a.d_h + j0);
-    uint16_t* Krow = reinterpret_cast<uint16_t*>(a.K) + (head * a.S_max + S) * a.d_h + j0;
-    uint16_t* Vrow = reinterpret_cast<uint16_t*>(a.V) + (head * a.S_max + S) * a.d_h + j0;
+    uint16_t* Krow = reinterpret_cast<uint16_t*>(a.K) + (head * a.S_stride + S) * a.d_h + j0;
+    uint16_t* Vrow = reinterpret_cast<uint16_t*>(a.V) + (head * a.S_stride + S) * a.d_h + j0;
     *reinterpret_cast<uint4*>(Krow) = kc;
     *reinterpret_cast<uint4*>(Vrow) = vc;
     // the same 8 key elements go down column S of the S-contiguous copy (2-byte stores)
@@ -47,8 +47,8 @@ __global__ __launch_bounds__(512) void append_one_row(const AppendArgs a) {
       const uint32_t kw[4] = {kc.x, kc.y, kc.z, kc.w};
 #pragma unroll
       for (int e = 0; e < 8; ++e)
-        flush_key_columns(reinterpret_cast<uint16_t*>(a.Kt) + head * a.d_h * (size_t)a.S_max,
-                          reinterpret_cast<const uint16_t*>(a.K) + head * a.S_max * (size_t)a.d_h, a.S_max, a.d_h, S + 1,
+        flush_key_columns(reinterpret_cast<uint16_t*>(a.Kt) + head * a.d_h * (size_t)a.S_stride,
+                          reinterpret_cast<const uint16_t*>(a.K) + head * a.S_stride * (size_t)a.d_h, a.S_stride, a.d_h, S + 1,
                           j0 + e, (uint16_t)((e & 1) ? (kw[e >> 1] >> 16) : (kw[e >> 1] & 0xffffu)));
     }
     // running mean: v_mean += (v - v_mean) / (S + 1)
@@ -94,9 +94,9 @@ __global__ __launch_bounds__(BT) void append_rows(const AppendArgs a) {
   const int sub = tid % CPR, prow = tid / CPR;
   const uint16_t* ksrc = reinterpret_cast<const uint16_t*>(a.k_new) + head * a.n_new * DH;
   const uint16_t* vsrc = reinterpret_cast<const uint16_t*>(a.v_new) + head * a.n_new * DH;
-  uint16_t* Kdst = reinterpret_cast<uint16_t*>(a.K) + (head * a.S_max + S) * DH;
-  uint16_t* Vdst = reinterpret_cast<uint16_t*>(a.V) + (head * a.S_max + S) * DH;
-  uint16_t* Ktdst = reinterpret_cast<uint16_t*>(a.Kt) + head * DH * a.S_max + S;
+  uint16_t* Kdst = reinterpret_cast<uint16_t*>(a.K) + (head * a.S_stride + S) * DH;
+  uint16_t* Vdst = reinterpret_cast<uint16_t*>(a.V) + (head * a.S_stride + S) * DH;
+  uint16_t* Ktdst = reinterpret_cast<uint16_t*>(a.Kt) + head * DH * (size_t)a.S_stride + S;
   double sum[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int n0 = 0; n0 < n; n0 += TILE) {
     const int rows = (n - n0) < TILE ? (n - n0) : TILE;
@@ -115,17 +115,17 @@ __global__ __launch_bounds__(BT) void append_rows(const AppendArgs a) {
     __syncthreads();
     if (a.Kt)
       for (int j = wave; j < DH; j += BT / 64)
-        if (lane < rows) Ktdst[(size_t)j * a.S_max + n0 + lane] = tile[lane * LD + j];
+        if (lane < rows) Ktdst[(size_t)j * a.S_stride + n0 + lane] = tile[lane * LD + j];
     __syncthreads();
   }
   // the up to 7 rows that were cached before this call and not yet in the S-contiguous copy
   if (a.Kt) {
     const int S_fl = S & ~7;
-    const uint16_t* Khead = reinterpret_cast<const uint16_t*>(a.K) + head * a.S_max * (size_t)DH;
-    uint16_t* Kthead = reinterpret_cast<uint16_t*>(a.Kt) + head * DH * (size_t)a.S_max;
+    const uint16_t* Khead = reinterpret_cast<const uint16_t*>(a.K) + head * a.S_stride * (size_t)DH;
+    uint16_t* Kthead = reinterpret_cast<uint16_t*>(a.Kt) + head * DH * (size_t)a.S_stride;
     for (int i = tid; i < (S - S_fl) * DH; i += BT) {
       const int e = i / DH, j = i - e * DH;
-      Kthead[(size_t)j * a.S_max + S_fl + e] = Khead[(size_t)(S_fl + e) * DH + j];
+      Kthead[(size_t)j * a.S_stride + S_fl + e] = Khead[(size_t)(S_fl + e) * DH + j];
     }
   }
 #pragma unroll
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(512) void append_one_row_tiled(const AppendArgs a) 
     const uint4 kc = load16(reinterpret_cast<const uint16_t*>(a.k_new) + head * a.d_h + j0);
     const uint4 vc = load16(reinterpret_cast<const uint16_t*>(a.v_new) + head * a.d_h + j0);
     uint16_t* stage = reinterpret_cast<uint16_t*>(a.Kt) + head * (size_t)(8 * a.d_h);
-    *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(a.V) + (head * a.S_max + S) * a.d_h + j0) = vc;
+    *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(a.V) + (head * a.S_stride + S) * a.d_h + j0) = vc;
     if (slot != 7) {
       *reinterpret_cast<uint4*>(stage + slot * a.d_h + j0) = kc;
     } else {               // the eighth row: this thread's 8 channels of the finished tile
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(512) void append_one_row_tiled(const AppendArgs a) 
 #pragma unroll
       for (int e = 0; e < 7; ++e) rows[e] = load16(stage + e * a.d_h + j0);
       rows[7] = kc;
-      store_tile_piece(reinterpret_cast<uint16_t*>(a.K) + (head * a.S_max + (size_t)(S - 7)) * a.d_h + (size_t)j0 * 8, rows);
+      store_tile_piece(reinterpret_cast<uint16_t*>(a.K) + (head * a.S_stride + (size_t)(S - 7)) * a.d_h + (size_t)j0 * 8, rows);
     }
     const float* vm = a.v_mean + head * a.d_h + j0;
     float* vo = a.v_mean_out + head * a.d_h + j0;
@@ -243,9 +243,9 @@ __global__ __launch_bounds__(BT) void append_rows_tiled(const AppendArgs a) {
   }
   const uint16_t* ksrc = reinterpret_cast<const uint16_t*>(a.k_new) + head * a.n_new * DH;
   const uint16_t* vsrc = reinterpret_cast<const uint16_t*>(a.v_new) + head * a.n_new * DH;
-  uint16_t* Kdst = reinterpret_cast<uint16_t*>(a.K) + head * a.S_max * (size_t)DH;
+  uint16_t* Kdst = reinterpret_cast<uint16_t*>(a.K) + head * a.S_stride * (size_t)DH;
   uint16_t* stage = reinterpret_cast<uint16_t*>(a.Kt) + head * (size_t)(8 * DH);
-  uint16_t* Vdst = reinterpret_cast<uint16_t*>(a.V) + (head * a.S_max + S) * DH;
+  uint16_t* Vdst = reinterpret_cast<uint16_t*>(a.V) + (head * a.S_stride + S) * DH;
   // keys, tile by tile
   const int sub = tid % CPR, e = (tid / CPR) & 7, tl = tid / (8 * CPR);
   const int g_first = S >> 3, g_last = (S + n - 1) >> 3;

@@ -21,7 +21,8 @@ struct DecodeArgs {
   const void* k_new; const void* v_new;          // non-null: fused append (one-launch decode step)
   float* v_mean_next; int32_t* seq_lens_next;
   void* out; float* alpha_out; int32_t* idx_out; int32_t* chan_out; int32_t* err;
-  int32_t B, H, H_kv, S_max, d_h, r, k, idx_stride;
+  int32_t B, H, H_kv, S_max, d_h, r, k, idx_stride;   // S_max: the bound on the lengths that LDS and workspace are sized for
+  int32_t S_stride;   // positions per head in K and V and per channel row in Kt (the buffers' own S_max, >= S_max)
   uint32_t flags;
   int32_t local_window;
   unsigned long long* clocks = nullptr;   // [workgroups][kStageStamps] time stamps; set only by a SPARQ_STAGE_CLOCKS build
@@ -36,7 +37,8 @@ struct AppendArgs {
   void* K; void* Kt; void* V; float* v_mean; int32_t* seq_lens;
   float* v_mean_out; int32_t* seq_lens_out;   // where the new means / lengths go (== v_mean / seq_lens: in place)
   const void* k_new; const void* v_new; const int32_t* n_new_per_seq; int32_t* err;
-  int32_t B, H_kv, S_max, d_h, n_new;
+  int32_t B, H_kv, S_max, d_h, n_new;   // S_max: no length may pass it
+  int32_t S_stride;   // positions per head in K and V and per channel row in Kt
   int32_t tiled;   // the tiled single-copy key layout: K holds tiles of 8 positions, Kt the rows of the newest < 8
 };
 
@@ -45,6 +47,7 @@ struct DenseArgs {
   float* partials;   // [B*H, n_split, d_h + 2]
   int32_t* err;
   int32_t B, H, H_kv, S_max, d_h, n_split, rows_per_split;
+  int32_t S_stride;   // positions per head in K and V
 };
 
 // two-level plan: spans of span_len positions (a multiple of 64, at most kLongSpan), at most kMaxSpans per sequence

@@ -108,6 +108,8 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
     }
   }
   int S = a.seq_lens[b];
+  // a length beyond the bound of this call that the buffers can hold is carried over as it is (clamped only here)
+  const int S_kept = (S > a.S_max && S <= a.S_stride) ? S : -1;
   if (S < 0 || S > a.S_max) {
     if (tid == 0) atomicOr(a.err, 8);
     S = S < 0 ? 0 : a.S_max;
@@ -117,7 +119,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   if (APPEND) {
     if (S + 1 <= a.S_max) { appended = true; S += 1; }
     else if (tid == 0) atomicOr(a.err, 1);
-    if (h == 0 && tid == 0) a.seq_lens_next[b] = S;
+    if (h == 0 && tid == 0) a.seq_lens_next[b] = S_kept >= 0 ? S_kept : S;
   }
   int kb = a.k_per_seq ? a.k_per_seq[b] : a.k;
   kb = kb < 1 ? 1 : (kb > a.k ? a.k : kb);
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   const int S_fl = ((APPEND && appended) ? S - 1 : S) & ~7, n_tail = S - S_fl, r8 = (a.r + 7) & ~7;
   // rows of K by position (two-copy layout), or the rows of the newest positions S_fl .. (tiled layout)
   const uint16_t* K_rows = TILED ? reinterpret_cast<const uint16_t*>(a.Kt) + kv_head * (size_t)(8 * DH) - (size_t)S_fl * DH
-                                 : reinterpret_cast<const uint16_t*>(a.K) + kv_head * a.S_max * (size_t)DH;
+                                 : reinterpret_cast<const uint16_t*>(a.K) + kv_head * a.S_stride * (size_t)DH;
   TailRow tail;
   const bool tail_is_new = APPEND && appended && wave == n_tail - 1;
   if (wave < n_tail) {
@@ -162,8 +164,8 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
 
   SPARQ_STAMP(1);
   // ---------------- stage 1 ----------------
-  const size_t row_bytes = TILED ? 16 : (size_t)a.S_max * 2;
-  const char* Kt_head = TILED ? reinterpret_cast<const char*>(a.K) + kv_head * a.S_max * (size_t)(DH * 2)
+  const size_t row_bytes = TILED ? 16 : (size_t)a.S_stride * 2;
+  const char* Kt_head = TILED ? reinterpret_cast<const char*>(a.K) + kv_head * a.S_stride * (size_t)(DH * 2)
                               : reinterpret_cast<const char*>(a.Kt) + kv_head * DH * row_bytes;
   float tmax = -INFINITY;
   auto finish = [&](int c, const float (&acc)[8]) {
@@ -215,8 +217,8 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   using G = RowGeometry<DH>;
   const int sub = lane % G::LPR;
   const int* list = reinterpret_cast<const int*>(L.keys);
-  const char* K_head = reinterpret_cast<const char*>(a.K) + kv_head * a.S_max * (size_t)(DH * 2) + sub * 16;
-  const char* V_head = reinterpret_cast<const char*>(a.V) + kv_head * a.S_max * (size_t)(DH * 2) + sub * 16;
+  const char* K_head = reinterpret_cast<const char*>(a.K) + kv_head * a.S_stride * (size_t)(DH * 2) + sub * 16;
+  const char* V_head = reinterpret_cast<const char*>(a.V) + kv_head * a.S_stride * (size_t)(DH * 2) + sub * 16;
   const float qscale = kLog2e / sqrtf((float)DH);
   float q8[8];
 #pragma unroll
@@ -254,18 +256,18 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
     a.v_mean_next[kv_head * DH + tid] = __uint_as_float(L.qry.mag[tid]);
     if (appended) {
       const uint16_t kc = L.knew[tid];
-      reinterpret_cast<uint16_t*>(a.V)[(kv_head * a.S_max + (S - 1)) * DH + tid] = L.vnew[tid];
+      reinterpret_cast<uint16_t*>(a.V)[(kv_head * a.S_stride + (S - 1)) * DH + tid] = L.vnew[tid];
       if (!TILED) {
-        reinterpret_cast<uint16_t*>(a.K)[(kv_head * a.S_max + (S - 1)) * DH + tid] = kc;
+        reinterpret_cast<uint16_t*>(a.K)[(kv_head * a.S_stride + (S - 1)) * DH + tid] = kc;
         // a step that completes a group of 8 positions copies it to Kt (one 16-byte store per channel row)
         if ((S & 7) == 0)
-          flush_key_columns(reinterpret_cast<uint16_t*>(a.Kt) + kv_head * DH * (size_t)a.S_max, K_rows, a.S_max, DH, S, tid, kc);
+          flush_key_columns(reinterpret_cast<uint16_t*>(a.Kt) + kv_head * DH * (size_t)a.S_stride, K_rows, a.S_stride, DH, S, tid, kc);
       } else if ((S & 7) != 0) {
         const_cast<uint16_t*>(K_rows)[(size_t)(S - 1) * DH + tid] = kc;        // row (S - 1) mod 8 of the small buffer
       } else {
         // the eighth row completes a tile: channel tid's 8 positions are 16 contiguous bytes of it
         const uint4 cols = gather_key_columns(K_rows, DH, S, tid, kc);
-        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(a.K) + (kv_head * a.S_max + (size_t)(S - 8)) * DH + (size_t)tid * 8) = cols;
+        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(a.K) + (kv_head * a.S_stride + (size_t)(S - 8)) * DH + (size_t)tid * 8) = cols;
       }
     }
   }

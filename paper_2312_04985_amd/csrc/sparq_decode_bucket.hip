@@ -194,12 +194,12 @@ __global__ __launch_bounds__(NT, 4) void bk_scores(const BucketArgs a) {
   if (wave < n_tail) {
     const uint16_t* krow = appended && wave == n_tail - 1
                                ? reinterpret_cast<const uint16_t*>(d.k_new) + kv_head * DH
-                               : reinterpret_cast<const uint16_t*>(d.K) + (kv_head * d.S_max + S_fl + wave) * (size_t)DH;
+                               : reinterpret_cast<const uint16_t*>(d.K) + (kv_head * d.S_stride + S_fl + wave) * (size_t)DH;
     tail = tail_row_issue(krow, chan, r8, lane);
   }
 
   const int end = p0 + len < S_fl ? p0 + len : S_fl;     // whole chunks of this span that are in Kt
-  const size_t row_bytes = (size_t)d.S_max * 2;
+  const size_t row_bytes = (size_t)d.S_stride * 2;
   const char* Kt_head = reinterpret_cast<const char*>(d.Kt) + kv_head * DH * row_bytes;
   float tmax = -INFINITY;
   const int c_begin = p0 >> 3, c_end = end > p0 ? end >> 3 : p0 >> 3;
@@ -663,8 +663,8 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) q8[e] = f[e] * qscale;
   }
-  const char* K_head = reinterpret_cast<const char*>(d.K) + kv_head * d.S_max * (size_t)(DH * 2) + sub * 16;
-  const char* V_head = reinterpret_cast<const char*>(d.V) + kv_head * d.S_max * (size_t)(DH * 2) + sub * 16;
+  const char* K_head = reinterpret_cast<const char*>(d.K) + kv_head * d.S_stride * (size_t)(DH * 2) + sub * 16;
+  const char* V_head = reinterpret_cast<const char*>(d.V) + kv_head * d.S_stride * (size_t)(DH * 2) + sub * 16;
   float m_run = -INFINITY, l_run = 0.0f;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   // positions are ascending, so the row being appended (position S - 1, not in the cache yet) can only be the
@@ -708,14 +708,17 @@ __global__ __launch_bounds__(DH) void bk_combine(const BucketArgs a) {
       d.v_mean_next[kv_head * DH + c] = vm;
       if (appended) {
         const uint16_t kc = reinterpret_cast<const uint16_t*>(d.k_new)[kv_head * DH + c];
-        uint16_t* K_rows = reinterpret_cast<uint16_t*>(d.K) + kv_head * d.S_max * (size_t)DH;
-        reinterpret_cast<uint16_t*>(d.V)[(kv_head * d.S_max + (S - 1)) * DH + c] = vcode;
+        uint16_t* K_rows = reinterpret_cast<uint16_t*>(d.K) + kv_head * d.S_stride * (size_t)DH;
+        reinterpret_cast<uint16_t*>(d.V)[(kv_head * d.S_stride + (S - 1)) * DH + c] = vcode;
         K_rows[(size_t)(S - 1) * DH + c] = kc;
         if ((S & 7) == 0)
-          flush_key_columns(reinterpret_cast<uint16_t*>(d.Kt) + kv_head * DH * (size_t)d.S_max, K_rows, d.S_max, DH, S, c, kc);
+          flush_key_columns(reinterpret_cast<uint16_t*>(d.Kt) + kv_head * DH * (size_t)d.S_stride, K_rows, d.S_stride, DH, S, c, kc);
       }
     }
-    if (h == 0 && c == 0) d.seq_lens_next[b] = S;
+    if (h == 0 && c == 0) {   // a length beyond the bound of this call that the buffers can hold is carried over as it is
+      const int S_in = d.seq_lens[b];
+      d.seq_lens_next[b] = (S_in > d.S_max && S_in <= d.S_stride) ? S_in : S;
+    }
   }
   if (S <= 0) return;                      // outputs written by bk_scores
   const float* parts = a.part_ws + (size_t)u * a.n_span * (DH + 2);

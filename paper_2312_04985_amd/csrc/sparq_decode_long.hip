@@ -98,10 +98,10 @@ __global__ __launch_bounds__(NT, 4) void long_scores(const LongArgs a) {
   const int n_tail = (S_fl >= p0 && S_fl < p0 + len) ? S - S_fl : 0;
   TailRow tail;
   if (wave < n_tail)
-    tail = tail_row_issue(reinterpret_cast<const uint16_t*>(d.K) + (kv_head * d.S_max + S_fl + wave) * (size_t)DH, chan, r8, lane);
+    tail = tail_row_issue(reinterpret_cast<const uint16_t*>(d.K) + (kv_head * d.S_stride + S_fl + wave) * (size_t)DH, chan, r8, lane);
 
   const int end = p0 + len < S_fl ? p0 + len : S_fl;     // whole chunks of this span that are in Kt
-  const size_t row_bytes = (size_t)d.S_max * 2;
+  const size_t row_bytes = (size_t)d.S_stride * 2;
   const char* Kt_head = reinterpret_cast<const char*>(d.Kt) + kv_head * DH * row_bytes;
   float tmax = -INFINITY;
   stream_channel_rows<T>(Kt_head, row_bytes, chan, qs, d.r, p0 >> 3, end > p0 ? end >> 3 : p0 >> 3, tid,

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a,
   const Window win = make_window(a.local_window, S, kq);
 
   // ---------------- pass A: per-head max and sum-exp of the approximate logits ----------------
-  const size_t row_bytes = (size_t)a.S_max * 2;
+  const size_t row_bytes = (size_t)a.S_stride * 2;
   const char* Kt_head = reinterpret_cast<const char*>(a.Kt) + kv_head * DH * row_bytes;
   const int n_chunks = S >> 3;   // whole chunks; the newest S mod 8 positions are not in Kt yet
   const int S_fl = S & ~7, n_tail = S - S_fl, r8 = (a.r + 7) & ~7;
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a,
 #pragma unroll
   for (int h = 0; h < G; ++h) tdot[h] = 0.0f;
   if (wave < n_tail) {
-    const TailRow tail = tail_row_issue(reinterpret_cast<const uint16_t*>(a.K) + (kv_head * a.S_max + S_fl + wave) * (size_t)DH,
+    const TailRow tail = tail_row_issue(reinterpret_cast<const uint16_t*>(a.K) + (kv_head * a.S_stride + S_fl + wave) * (size_t)DH,
                                         L.chan, r8, lane);
 #pragma unroll
     for (int h = 0; h < G; ++h) tdot[h] = tail_row_dot<T>(tail, L.qs + h * DH, r8, lane);
@@ -233,8 +233,8 @@ __global__ __launch_bounds__(NT, 2) void sparq_decode_shared(const DecodeArgs a,
   constexpr int UNR = 2, GROUP = Geo::RPI * UNR;
   const int sub = lane % Geo::LPR, slot = wave * Geo::RPW + lane / Geo::LPR;
   const int* list = reinterpret_cast<const int*>(L.keys);
-  const char* K_head = reinterpret_cast<const char*>(a.K) + kv_head * a.S_max * (size_t)(DH * 2) + sub * 16;
-  const char* V_head = reinterpret_cast<const char*>(a.V) + kv_head * a.S_max * (size_t)(DH * 2) + sub * 16;
+  const char* K_head = reinterpret_cast<const char*>(a.K) + kv_head * a.S_stride * (size_t)(DH * 2) + sub * 16;
+  const char* V_head = reinterpret_cast<const char*>(a.V) + kv_head * a.S_stride * (size_t)(DH * 2) + sub * 16;
   const float qscale = kLog2e / sqrtf((float)DH);
   float q8[G][8];   // query slices, exp2 domain
   float m_run[G], l_run[G], acc[G][8];

@@ -88,12 +88,12 @@ __global__ __launch_bounds__(NT, 2) void gs_logits(const GsArgs a) {
   if (wave < n_tail) {
     const uint16_t* krow = appended && wave == n_tail - 1
                                ? reinterpret_cast<const uint16_t*>(d.k_new) + kv_head * DH
-                               : reinterpret_cast<const uint16_t*>(d.K) + (kv_head * d.S_max + S_fl + wave) * (size_t)DH;
+                               : reinterpret_cast<const uint16_t*>(d.K) + (kv_head * d.S_stride + S_fl + wave) * (size_t)DH;
     tail = tail_row_issue(krow, chan, r8, lane);
   }
 
   const int end = p0 + len < S_fl ? p0 + len : S_fl;     // whole chunks of this span that are in Kt
-  const size_t row_bytes = (size_t)d.S_max * 2;
+  const size_t row_bytes = (size_t)d.S_stride * 2;
   const char* Kt_head = reinterpret_cast<const char*>(d.Kt) + kv_head * DH * row_bytes;
   float* z_unit = a.z_ws + u0 * (size_t)d.S_max;
   float mt[G], zt[G];
@@ -428,8 +428,8 @@ __global__ __launch_bounds__(NT, 2) void gs_gather(const GsArgs a) {
   constexpr int UNR = 2, GROUP = Geo::RPI * UNR;
   const int sub = lane % Geo::LPR, slot = wave * Geo::RPW + lane / Geo::LPR;
   const int* list = a.list_ws + (size_t)ukv * a.list_stride;
-  const char* K_head = reinterpret_cast<const char*>(d.K) + kv_head * d.S_max * (size_t)(DH * 2) + sub * 16;
-  const char* V_head = reinterpret_cast<const char*>(d.V) + kv_head * d.S_max * (size_t)(DH * 2) + sub * 16;
+  const char* K_head = reinterpret_cast<const char*>(d.K) + kv_head * d.S_stride * (size_t)(DH * 2) + sub * 16;
+  const char* V_head = reinterpret_cast<const char*>(d.V) + kv_head * d.S_stride * (size_t)(DH * 2) + sub * 16;
   const float qscale = kLog2e / sqrtf((float)DH);
   float q8[G][8], m_run[G], l_run[G], acc[G][8];
 #pragma unroll

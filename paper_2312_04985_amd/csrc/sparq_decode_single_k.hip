@@ -138,8 +138,8 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_single_k(const DecodeArgs 
   // ---------------- stage 1: whole key rows, masked query ----------------
   using G = RowGeometry<DH>;
   const int sub = lane % G::LPR;
-  const char* K_head = reinterpret_cast<const char*>(a.K) + kv_head * a.S_max * (size_t)(DH * 2) + sub * 16;
-  const char* V_head = reinterpret_cast<const char*>(a.V) + kv_head * a.S_max * (size_t)(DH * 2) + sub * 16;
+  const char* K_head = reinterpret_cast<const char*>(a.K) + kv_head * a.S_stride * (size_t)(DH * 2) + sub * 16;
+  const char* V_head = reinterpret_cast<const char*>(a.V) + kv_head * a.S_stride * (size_t)(DH * 2) + sub * 16;
   float qm8[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) qm8[e] = L.qmask[sub * 8 + e];

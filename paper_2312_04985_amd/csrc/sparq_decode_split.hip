@@ -52,8 +52,8 @@ __global__ __launch_bounds__(NT, 4) void split_gather(const SplitArgs a) {
   const int per = (kq + a.n_split - 1) / a.n_split;
   const int n0 = s * per < kq ? s * per : kq;
   const int n1 = n0 + per < kq ? n0 + per : kq;
-  const char* K_head = reinterpret_cast<const char*>(d.K) + kv_head * d.S_max * (size_t)(DH * 2) + sub * 16;
-  const char* V_head = reinterpret_cast<const char*>(d.V) + kv_head * d.S_max * (size_t)(DH * 2) + sub * 16;
+  const char* K_head = reinterpret_cast<const char*>(d.K) + kv_head * d.S_stride * (size_t)(DH * 2) + sub * 16;
+  const char* V_head = reinterpret_cast<const char*>(d.V) + kv_head * d.S_stride * (size_t)(DH * 2) + sub * 16;
   float m_run = -INFINITY, l_run = 0.0f;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   attend_rows<T, DH>(K_head, V_head, a.list_ws + (size_t)u * d.S_max, n0, n1, q8, lane, wave, m_run, l_run, acc);

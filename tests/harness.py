@@ -216,14 +216,14 @@ def check_positions_shared(gpu_idx: np.ndarray, ref: O.SparqResult, Kh: np.ndarr
 
 
 def compare_decode(b: Built, q: torch.Tensor, *, flags: int = 0, check_state: bool = True, local_window: int = 0,
-                   step_rows=None) -> dict:
+                   step_rows=None, S_bound: int = 0) -> dict:
     """Run sparq_decode and dense_decode on the GPU and the oracle on the host, on the whole batch; assert
     parity of every unit.  With step_rows = (k_new, v_new) the GPU runs sparq_decode_step instead of
     sparq_decode, and `b` describes the cache as it must be AFTER the append of those rows."""
     w, c = b.w, b.cache
     dev_k = None if b.k_per_seq is None else b.k_per_seq.to(c.device)
     kq_max = int(torch.minimum(b.k_per_seq if b.k_per_seq is not None else torch.full_like(b.seq_lens, w.k), b.seq_lens).max())
-    c.with_params(w.r, w.k, flags, local_window)
+    c.with_params(w.r, w.k, flags, local_window, S_bound)    # S_bound: the caller's bound on the lengths (0: the buffers' S_max)
     if step_rows is None:
         out, alpha, idx, chan = c.decode(q, dev_k, aux=True, idx_stride=max(kq_max, 1))
     else:

@@ -32,7 +32,7 @@ def test_status_strings():
 
 
 def shape(**kw):
-    d = dict(B=2, H=4, H_kv=2, S_max=128, d_h=128, r=16, k=8, dtype=0, flags=0, local_window=0)
+    d = dict(B=2, H=4, H_kv=2, S_max=128, d_h=128, r=16, k=8, dtype=0, flags=0, local_window=0, S_bound=0)
     d.update(kw)
     return B.SparqShape(*[d[f] for f, _ in B.SparqShape._fields_])
 
@@ -55,6 +55,20 @@ def test_stage_clocks_exist_only_in_a_profiling_build():
         assert need.value >= 65536 + 8 * 9 * 8
 
 
+def test_a_bound_on_the_lengths_sizes_plan_and_workspace():
+    """With S_bound set, the plan and the workspace are those of a cache of S_bound positions."""
+    many = dict(B=64, H=32, H_kv=32, r=16, k=256)
+    assert "one workgroup per head" in B.sparq_decode_plan(shape(S_max=8192, **many))
+    assert "two-level" in B.sparq_decode_plan(shape(S_max=65536, **many))
+    assert "one workgroup per head" in B.sparq_decode_plan(shape(S_max=65536, S_bound=8192, **many))
+    assert B.sparq_workspace_bytes(shape(S_max=65536, S_bound=8192, **many)) == B.sparq_workspace_bytes(shape(S_max=8192, **many))
+    few = dict(B=1, H=32, H_kv=8, r=32, k=2048, dtype=1)
+    assert "digit-bucket" in B.sparq_decode_plan(shape(S_max=131072, S_bound=32768, **few))
+    assert B.sparq_workspace_bytes(shape(S_max=131072, S_bound=32768, **few)) == B.sparq_workspace_bytes(shape(S_max=32768, **few))
+    assert B.sparq_workspace_bytes(shape(S_max=131072, S_bound=131072, **few)) == B.sparq_workspace_bytes(shape(S_max=131072, **few))
+    assert "one workgroup per head" in B.sparq_decode_plan(shape(S_max=131072, S_bound=4096, **few))
+
+
 def test_workspace_bytes_and_shape_validation():
     need = B.sparq_workspace_bytes(shape())
     assert need >= 256 + 2 * 4 * (128 + 2) * 4
@@ -62,6 +76,7 @@ def test_workspace_bytes_and_shape_validation():
     for bad, code in [(dict(S_max=100), B.SPARQ_EINVAL), (dict(H=5), B.SPARQ_EINVAL), (dict(r=0), B.SPARQ_EINVAL),
                       (dict(r=129), B.SPARQ_EINVAL), (dict(k=0), B.SPARQ_EINVAL), (dict(dtype=2), B.SPARQ_EINVAL),
                       (dict(flags=128), B.SPARQ_EINVAL), (dict(flags=32 | 64), B.SPARQ_EINVAL), (dict(flags=8 | 16), B.SPARQ_EINVAL), (dict(local_window=-1), B.SPARQ_EINVAL),
+                      (dict(S_bound=-64), B.SPARQ_EINVAL), (dict(S_bound=100), B.SPARQ_EINVAL), (dict(S_bound=192), B.SPARQ_EINVAL),
                       (dict(B=0), B.SPARQ_EINVAL), (dict(d_h=80, r=16), B.SPARQ_EUNSUPPORTED)]:
         with pytest.raises(B.SparqError) as e:
             B.sparq_workspace_bytes(shape(**bad))

@@ -803,3 +803,88 @@ def test_bulk_append_after_single_appends_completes_the_key_copy():
     Hn.check_cache_state(b)
     q = W.draw_queries(w, K_src, seq, q_scale=0.02)[0]
     say(Hn.compare_decode(b, q))
+
+
+# ------------------------------------------------------------------ a bound on the lengths below the buffers' S_max
+
+SH, K1, TK = B.SPARQ_FLAG_GQA_SHARED, B.SPARQ_FLAG_SINGLE_K, B.SPARQ_FLAG_TILED_K
+
+
+@pytest.mark.parametrize("name,kw,S_max,plan,flags,step", [
+    ("bound_fused", dict(B=3, H=4, H_kv=4, d_h=128, S=1000, r=16, k=64, dtype="f16"), 8192, "sparq_decode_fused", 0, True),
+    ("bound_fused_gqa_d256", dict(B=2, H=4, H_kv=2, d_h=256, S=1500, r=64, k=200, dtype="bf16"), 4096, "sparq_decode_fused", 0, False),
+    ("bound_bucket", dict(B=1, H=4, H_kv=2, d_h=128, S=9000, r=16, k=300, dtype="f16"), 20480, "digit-bucket", 0, True),
+    ("bound_two_level", dict(B=5, H=32, H_kv=32, d_h=64, S=36001, r=8, k=100, dtype="f16"), 40960, "two-level", 0, True),
+    ("bound_shared", dict(B=2, H=8, H_kv=2, d_h=128, S=3000, r=16, k=128, dtype="bf16"), 16384, "one workgroup per KV head", SH, True),
+    ("bound_shared_bucket", dict(B=1, H=8, H_kv=2, d_h=128, S=9000, r=16, k=300, dtype="bf16"), 32768, "grouped-query rule on the digit-bucket", SH, True),
+    ("bound_shared_split", dict(B=5, H=32, H_kv=8, d_h=64, S=17000, r=8, k=200, dtype="f16"), 20480, "several workgroups per KV head", SH, False),
+    ("bound_single_k", dict(B=2, H=4, H_kv=4, d_h=128, S=1000, r=16, k=64, dtype="f16"), 4096, "stored once", K1, True),
+    ("bound_tiled", dict(B=2, H=4, H_kv=4, d_h=128, S=1000, r=16, k=64, dtype="f16"), 4096, "sparq_decode_fused", TK, True),
+])
+def test_bound_on_the_lengths_below_the_buffers_s_max(name, kw, S_max, plan, flags, step):
+    """Buffers allocated for S_max positions, the call told that no sequence passes S_bound < S_max: the kernels
+    and the workspace are those of a cache of S_bound positions, the strides those of S_max.  Checked against the
+    oracle, bit for bit against the same data in buffers of exactly S_bound positions, and over one step."""
+    w = W.Workload(name, seed=61, **kw)
+    S_bound = W.round_up(w.S + 1, 64)
+    layout = flags & (K1 | TK)
+    seq = torch.tensor([max(1, w.S - 37 * i) for i in range(w.B)], dtype=torch.int32)
+    say(f"[case] {name} S_max={S_max} S_bound={S_bound} flags={flags}")
+    wide = Hn.build_cache(w, seq_lens=seq, S_max=S_max, v_offset=True, flags=layout)
+    tight = Hn.build_cache(w, seq_lens=seq, S_max=S_bound, v_offset=True, flags=layout)
+    sh_wide = B.make_shape(w.B, w.H, w.H_kv, S_max, w.d_h, w.r, w.k, w.dtype_code, flags, 0, S_bound)
+    sh_tight = B.make_shape(w.B, w.H, w.H_kv, S_bound, w.d_h, w.r, w.k, w.dtype_code, flags)
+    assert plan in B.sparq_decode_plan(sh_wide) and B.sparq_decode_plan(sh_wide) == B.sparq_decode_plan(sh_tight)
+    assert B.sparq_workspace_bytes(sh_wide) == B.sparq_workspace_bytes(sh_tight)
+    q = W.draw_queries(w, wide.K_src, seq, q_scale=0.02)[0]
+    say("   ", Hn.compare_decode(wide, q, flags=flags, S_bound=S_bound))
+    tight.cache.with_params(w.r, w.k, flags)
+    o_w, a_w, i_w, c_w = wide.cache.decode(q, aux=True)
+    o_t, a_t, i_t, c_t = tight.cache.decode(q, aux=True)
+    torch.cuda.synchronize()
+    assert torch.equal(o_w.view(torch.int16), o_t.view(torch.int16)) and torch.equal(i_w, i_t) and torch.equal(a_w, a_t)
+    if not step:
+        return
+    kn, vn = W.draw_kv(W.scaled(w, seed=62), "cuda", n_rows=1, v_offset=True)
+    Kg, Vg = torch.cat([wide.K_src, kn], dim=2), torch.cat([wide.V_src, vn], dim=2)
+    for i in range(w.B):
+        Kg[i, :, int(seq[i])] = kn[i, :, 0]; Vg[i, :, int(seq[i])] = vn[i, :, 0]
+    grown = Hn.Built(w, wide.cache, Kg, Vg, seq + 1, None)
+    rows = (kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous())
+    say("    step:", Hn.compare_decode(grown, q, flags=flags, S_bound=S_bound, step_rows=rows))
+    o_t = tight.cache.step(rows[0], rows[1], q)
+    o_w = wide.cache.decode(q)
+    torch.cuda.synchronize()
+    assert torch.equal(wide.cache.v_mean, tight.cache.v_mean) and tight.cache.error_flags() == 0
+
+
+def test_lengths_beyond_the_bound_are_reported():
+    """The bound is treated as S_max is without it: a longer sequence is clamped for the call and flagged (its stored
+    length stays), a step whose append would pass the bound leaves that sequence alone and flags that."""
+    w = W.Workload("bound_errors", 2, 4, 4, 128, 1030, 16, 64, "f16", seed=63)
+    seq = torch.tensor([1000, 1030], dtype=torch.int32)
+    b = Hn.build_cache(w, seq_lens=seq, S_max=2048, v_offset=True)
+    q = W.draw_queries(w, b.K_src, seq, q_scale=0.02)[0]
+    q[1, 0] = (b.K_src[1, 0, 1027].float() * 0.05).to(q.dtype)       # position 1027 is the best match of one head
+    ref, _, idx_ref, _ = b.cache.decode(q, aux=True)
+    torch.cuda.synchronize()
+    assert b.cache.error_flags() == 0 and 1027 in idx_ref[1, 0].tolist()
+    b.cache.with_bound(1024)
+    out, _, idx, _ = b.cache.decode(q, aux=True)
+    torch.cuda.synchronize()
+    assert b.cache.error_flags() == B.SPARQ_ERR_BAD_SEQ_LEN
+    assert torch.equal(out[0].view(torch.int16), ref[0].view(torch.int16))      # the sequence within the bound is served as before
+    assert int(idx[1].max()) < 1024                                              # the other one over its first 1024 positions
+    # a step at the bound: sequence 0 grows to 1001, sequence 1 (beyond the bound) takes no row and keeps its length
+    kn, vn = W.draw_kv(W.scaled(w, seed=64), "cuda", n_rows=1)
+    K_before = b.cache.K[1, :, 1030].clone()
+    b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q)
+    torch.cuda.synchronize()
+    flags = b.cache.error_flags()
+    assert flags & B.SPARQ_ERR_APPEND_FULL and flags & B.SPARQ_ERR_BAD_SEQ_LEN
+    assert b.cache.seq_lens.cpu().tolist() == [1001, 1030] and torch.equal(b.cache.K[0, :, 1000], kn[0, :, 0])
+    assert torch.equal(b.cache.K[1, :, 1030], K_before)
+    b.cache.with_bound(0)                                                        # without the bound everything is served again
+    out2, _, idx2, _ = b.cache.decode(q, aux=True)
+    torch.cuda.synchronize()
+    assert b.cache.error_flags() == 0 and 1027 in idx2[1, 0].tolist()
