@@ -742,15 +742,19 @@ def test_random_shape_and_options(case):
     w = W.Workload(f"rand{case}", Bn, H_kv * g, H_kv, d_h, S, r, k, dtype, seed=2000 + case, k_div=k_div)
     seq = torch.tensor([max(1, int(S * f)) for f in [1.0] + list(rng.uniform(0.05, 1.0, Bn - 1))], dtype=torch.int32)
     S_max = W.round_up(S + 8, 64)
-    say(f"[random {case}] B={Bn} H={w.H}/{H_kv} d_h={d_h} S={S} r={r} k={k} {dtype} flags={flags} l={window} "
+    rng2 = np.random.default_rng(5000 + case)       # (a generator of its own: the draws above stay what they were)
+    S_bound = 0
+    if rng2.random() < 0.35:                        # buffers longer than the bound the calls are given
+        S_bound, S_max = S_max, S_max + 64 * int(rng2.integers(1, 40))
+    say(f"[random {case}] S_max={S_max} S_bound={S_bound} B={Bn} H={w.H}/{H_kv} d_h={d_h} S={S} r={r} k={k} {dtype} flags={flags} l={window} "
         f"singles={singles} k_div={k_div} seq={seq.tolist()}")
     b = Hn.build_cache(w, seq_lens=seq, S_max=S_max, v_offset=True, single_appends=singles,
                        flags=flags & B.SPARQ_FLAG_SINGLE_K)
     q = W.draw_queries(w, b.K_src, b.seq_lens, n=2, q_scale=float(rng.choice([1.0, 0.05, 0.01])))
-    say("   ", Hn.compare_decode(b, q[0], flags=flags, local_window=window))
+    say("   ", Hn.compare_decode(b, q[0], flags=flags, local_window=window, S_bound=S_bound))
     # one step: the new row lands at S_b of every sequence
     kn, vn = W.draw_kv(W.scaled(w, seed=3000 + case), "cuda", n_rows=1, v_offset=True)
-    b.cache.with_params(w.r, w.k, flags, window)
+    b.cache.with_params(w.r, w.k, flags, window, S_bound)
     kps_dev = None if b.k_per_seq is None else b.k_per_seq.cuda()
     out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q[1], kps_dev)
     torch.cuda.synchronize()
@@ -758,7 +762,7 @@ def test_random_shape_and_options(case):
     for i in range(Bn):
         Kg[i, :, int(seq[i])] = kn[i, :, 0]; Vg[i, :, int(seq[i])] = vn[i, :, 0]
     grown = Hn.Built(w, b.cache, Kg, Vg, b.seq_lens + 1, b.k_per_seq)
-    st = Hn.compare_decode(grown, q[1], flags=flags, local_window=window)
+    st = Hn.compare_decode(grown, q[1], flags=flags, local_window=window, S_bound=S_bound)
     say("   ", st)
     again = b.cache.decode(q[1], kps_dev)
     assert ((out.float() - again.float()).abs() <= 2.0 ** -7 * again.float().abs() + 1e-6).all()
