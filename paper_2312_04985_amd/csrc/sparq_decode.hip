@@ -91,6 +91,7 @@ __global__ __launch_bounds__(NT, 4) void sparq_decode_fused(const DecodeArgs a) 
   } else if ((U & 7) == 0) {
     u = (u & 7) * (U >> 3) + (u >> 3);
   }
+  u = __builtin_amdgcn_readfirstlane(u);   // the same in every lane (also where it came through LDS): keep what follows scalar
   const int b = u / a.H, h = u - b * a.H;
   const int hk = h / (a.H / a.H_kv);
   const size_t kv_head = (size_t)b * a.H_kv + hk;
