@@ -389,11 +389,19 @@ __device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wsum, 
 
 // Ordered compaction of the selected positions into list[0..kq) (ascending) and
 // alpha = (sum over the selected of exp((d - dmax)/tau)) / (sum over all): Step 3's weight.
-// One sweep covers NT chunks (thread tid owns chunk base + tid), with one workgroup scan of the
-// packed (above-threshold, equal-to-threshold) counts per sweep.  (Wider sweeps with fewer barriers
-// were measured and are not faster: the sweep is bound by its arithmetic, not by the barrier.)
-// `list` may be the key array itself: the list overwrites it from the front; a write never lands
-// beyond the position it records and all reads of a sweep precede its writes (the scan's barrier).
+// A lane owns m = ceil(chunks / NT) <= 4 consecutive chunks per sweep, so lane order is position order and one
+// workgroup scan of the packed (above-threshold, equal-to-threshold) counts orders a whole sweep of 8 m NT
+// positions: one barrier for lengths up to 16 384, whatever the length is a multiple of.  (Sweeps of NT chunks,
+// one per lane, needed ceil(S / 4096) scans, and a last sweep of a few chunks still cost 0.5 us of one wave's
+// dependent arithmetic: 3-4 us per launch at a length just above a multiple of 4096 with 2048 heads.)
+// Before the scan a lane reads its keys and sums the softmax weights: of all keys, of the keys above the
+// threshold (taken for sure), and of the keys equal to it on the decided bits; after it only the positions are
+// written, from two bit masks.  Which of the equal keys are taken (the first `need` by position) does not matter
+// for the sums: either all of them are (the select stopped early because the whole bin is taken), or all 32 bits
+// are decided and they share one weight.
+// `list` may be the key array itself: the list overwrites it from the front; a write never lands beyond the
+// position it records and all reads of a sweep precede its writes (the scan's barrier).  With key_out the keys
+// are read again after the scan: list must then be another array.
 // Ends with a barrier that also publishes the list.  esc = log2(e) / tau.  With WITH_ALPHA = false only
 // the list is produced (the grouped-query kernel gets alpha per query head elsewhere) and 0 is returned.
 // Positions >= forced_from (the local window) are taken whatever their keys; the predicate applies to
@@ -407,37 +415,44 @@ __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t
                                                   int lane, int wave, uint32_t* key_out = nullptr, int pos_base = 0,
                                                   float* sums_out = nullptr) {
   const int n_chunks = (S + 7) >> 3;
-  float zsum = 0.0f, asum = 0.0f;
+  int m = (n_chunks + NT - 1) / NT;
+  m = m > 4 ? 4 : m;
+  float zsum = 0.0f, asum = 0.0f, esum = 0.0f;
   uint32_t run_gt = 0, run_eq = 0;
   int sweep = 0;
-  for (int c0 = 0; c0 < n_chunks; c0 += NT, ++sweep) {
-    const int c = c0 + tid;
-    uint32_t kx[8];
-    if (c < n_chunks) {
-      const uint4* src = reinterpret_cast<const uint4*>(keys + c * 8);
-      const uint4 lo = src[0], hi = src[1];
-      kx[0] = lo.x; kx[1] = lo.y; kx[2] = lo.z; kx[3] = lo.w;
-      kx[4] = hi.x; kx[5] = hi.y; kx[6] = hi.z; kx[7] = hi.w;
-    } else {
+  for (int c0 = 0; c0 < n_chunks; c0 += NT * m, ++sweep) {
+    const int cb = c0 + tid * m;                 // the lane's first chunk of this sweep
+    uint32_t gt_bits = 0, eq_bits = 0;           // bit 8 i + e: key e of the lane's i-th chunk
 #pragma unroll
-      for (int e = 0; e < 8; ++e) kx[e] = 0u;
-    }
-    uint32_t n_gt = 0, n_eq = 0, gt_bits = 0, eq_bits = 0;
+    for (int i = 0; i < 4; ++i) {
+      const int c = cb + i;
+      if (i < m && c < n_chunks) {
+        const uint4* src = reinterpret_cast<const uint4*>(keys + c * 8);
+        const uint4 lo = src[0], hi = src[1];
+        const uint32_t kx[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const bool valid = (c * 8 + e) < S && c < n_chunks;
-      const bool old = (c * 8 + e) < forced_from;
-      const uint32_t hi_bits = kx[e] & pmask;
-      const bool g = valid && (hi_bits > pval || !old), q = valid && old && hi_bits == pval;
-      gt_bits |= (uint32_t)g << e; eq_bits |= (uint32_t)q << e;
-      n_gt += g; n_eq += q;
+        for (int e = 0; e < 8; ++e) {
+          const bool valid = (c * 8 + e) < S;
+          const bool old = (c * 8 + e) < forced_from;
+          const uint32_t hi_bits = kx[e] & pmask;
+          const bool g = valid && (hi_bits > pval || !old), q = valid && old && hi_bits == pval;
+          gt_bits |= (uint32_t)g << (8 * i + e); eq_bits |= (uint32_t)q << (8 * i + e);
+          if (WITH_ALPHA) {
+            const float w = exp2_weight((key_to_float(kx[e]) - dmax) * esc);
+            zsum += valid ? w : 0.0f;
+            asum += g ? w : 0.0f;
+            esum += q ? w : 0.0f;
+          }
+        }
+      }
     }
     uint32_t total;
-    const uint32_t ex = block_scan_excl(n_gt | (n_eq << 16), sl.wcnt + (sweep & 1) * NW, lane, wave, &total);
+    const uint32_t ex = block_scan_excl((uint32_t)__popc(gt_bits) | ((uint32_t)__popc(eq_bits) << 16),
+                                        sl.wcnt + (sweep & 1) * NW, lane, wave, &total);
     const uint32_t gt_before = run_gt + (ex & 0xffffu);
-    uint32_t eq_before = run_eq + (ex >> 16);
+    const uint32_t eq_before = run_eq + (ex >> 16);
     uint32_t o = gt_before + (eq_before < (uint32_t)need ? eq_before : (uint32_t)need);
-    // the taken keys of this chunk: everything above the threshold and the first equal keys while they are needed
+    // the taken keys of this lane: everything above the threshold and the first equal keys while they are needed
     uint32_t take_bits = gt_bits;
     if (eq_bits) {
       uint32_t eb = eq_bits;
@@ -446,32 +461,12 @@ __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t
         take_bits |= low; eb ^= low;
       }
     }
-    if (WITH_ALPHA) {   // softmax weights of all 8 keys, without branches
-      const int n_valid = c < n_chunks ? S - c * 8 : 0;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float w = exp2_weight((key_to_float(kx[e]) - dmax) * esc);
-        w = e < n_valid ? w : 0.0f;
-        zsum += w;
-        asum += ((take_bits >> e) & 1u) ? w : 0.0f;
-      }
-    }
-    if (key_out == nullptr) {   // few keys are taken: visit only those
-      for (uint32_t tb = take_bits; tb; tb &= tb - 1) {
-        const int pos = pos_base + c * 8 + (__ffs(tb) - 1);
-        list[o] = (uint32_t)pos;
-        if (idx_out && (int)o < idx_stride) idx_out[o] = pos;
-        ++o;
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-        if ((take_bits >> e) & 1u) {
-          list[o] = (uint32_t)(pos_base + c * 8 + e);
-          key_out[o] = kx[e];
-          if (idx_out && (int)o < idx_stride) idx_out[o] = pos_base + c * 8 + e;
-          ++o;
-        }
+    for (uint32_t tb = take_bits; tb; tb &= tb - 1) {
+      const int at = cb * 8 + (__ffs(tb) - 1);
+      list[o] = (uint32_t)(pos_base + at);
+      if (key_out) key_out[o] = keys[at];
+      if (idx_out && (int)o < idx_stride) idx_out[o] = pos_base + at;
+      ++o;
     }
     run_gt += total & 0xffffu;
     run_eq += total >> 16;
@@ -480,12 +475,16 @@ __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t
     __syncthreads();
     return 0.0f;
   }
+  // run_eq is now the number of equal keys in the whole array, the same in every thread
+  const bool all_equal_taken = (uint32_t)need >= run_eq;
+  if (all_equal_taken) asum += esum;
   zsum = wave_sum(zsum); asum = wave_sum(asum);
   if (lane == 0) { sl.red[wave] = zsum; sl.red[NW + wave] = asum; }
   __syncthreads();
   float zt = 0.0f, at = 0.0f;
 #pragma unroll
   for (int w = 0; w < NW; ++w) { zt += sl.red[w]; at += sl.red[NW + w]; }
+  if (!all_equal_taken) at += (float)need * exp2_weight((key_to_float(pval) - dmax) * esc);
   if (sums_out) { sums_out[0] = zt; sums_out[1] = at; }
   return at / zt;
 }
