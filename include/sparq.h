@@ -171,8 +171,9 @@ int sparq_kv_append(const sparq_shape* shape, const sparq_cache* cache, const vo
  *   Step 3  alpha = sum_{i in i2} s_hat_i;  y = alpha y3 + (1 - alpha) v_mean
  * Arithmetic is fp32 on the 16-bit inputs; `out` is rounded to nearest-even.
  * Sizes: every plan keeps 4 bytes per position (or per candidate) of its unit of work in LDS.  One
- * workgroup per head serves S_max up to about 35 000.  Batches of at most 128 (sequence, head) units with
- * S_max >= 8192 are spread over spans of up to 8192 positions (at most 64 spans: S_max <= 524 288, any k).
+ * workgroup per head serves S_max up to about 35 000.  Few (sequence, head) units with long caches (at most 96
+ * from S_max = 16 384, at most 64 from 12 288, at most 128 beyond what one workgroup holds) are spread over spans of
+ * up to 8192 positions (at most 64 spans: S_max <= 524 288, any k).
  * Larger batches with longer caches are selected in two levels (spans of 8192 positions, at most 64 of
  * them, ceil(S_max / 8192) * min(k, 8192) candidates <= about 36 000: e.g. S_max = 524 288 at k = 512), also
  * under SPARQ_FLAG_GQA_SHARED.  SPARQ_FLAG_SINGLE_K and SPARQ_FLAG_TILED_K stop at about 35 000.

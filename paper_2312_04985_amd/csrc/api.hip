@@ -205,8 +205,18 @@ PlanInfo choose_plan(const sparq_shape* s) {
     if (one_wg) p.plan = kPlanShared;
     return p;
   }
-  if ((int64_t)s->B * s->H <= kSplitMaxUnits && s->S_max >= 8192 && bucket_plan(s, lds_max, &p)) { p.plan = kPlanBucket; return p; }
-  if (decode_lds_bytes(s->S_max, s->d_h) <= lds_max) { p.plan = kPlanFused; return p; }
+  // Few units with long caches: the digit-bucket plan, where it was measured faster than one workgroup per unit
+  // (H = 32, r = 32, k = S / 16, bucket / one-workgroup us per decode; S = 8192: 29/27, 32/29, 36/31, 41/32 at 32, 64,
+  // 96, 128 units; 12 288: 30/37, 36/39, 43/43, 49/43; 16 384: 33/46, 41/51, 49/55, 59/59; 24 576: 36/65, 48/70,
+  // 63/77, 95/79; 32 768: 41/82, 59/89, 94/98, 116/103), and whatever one workgroup's LDS cannot hold.
+  const int64_t units = (int64_t)s->B * s->H;
+  const bool one_wg_fits = decode_lds_bytes(s->S_max, s->d_h) <= lds_max;
+  const bool bucket_faster = (s->S_max >= 16384 && units <= 96) || (s->S_max >= 12288 && units <= 64);
+  if (units <= kSplitMaxUnits && s->S_max >= 8192 && (bucket_faster || !one_wg_fits) && bucket_plan(s, lds_max, &p)) {
+    p.plan = kPlanBucket;
+    return p;
+  }
+  if (one_wg_fits) { p.plan = kPlanFused; return p; }
   if (two_level_plan(s, kLongSpan, lds_max, &p)) p.plan = kPlanLong;
   return p;
 }

@@ -371,7 +371,7 @@ def test_grouped_query_rule_on_the_digit_bucket_plan_steps_and_ties():
     ("gqa_bf16", dict(B=2, H=8, H_kv=2, d_h=128, S=4100, r=32, k=512, dtype="bf16")),
     ("d256", dict(B=2, H=2, H_kv=2, d_h=256, S=1500, r=64, k=200, dtype="bf16")),
     ("d64_k_ge_s", dict(B=2, H=4, H_kv=2, d_h=64, S=40, r=8, k=64, dtype="f16")),
-    ("split_plan", dict(B=1, H=4, H_kv=2, d_h=128, S=9000, r=16, k=300, dtype="f16")),
+    ("split_plan", dict(B=1, H=4, H_kv=2, d_h=128, S=12400, r=16, k=300, dtype="f16")),
 ])
 def test_decode_step_equals_append_then_decode(name, kw):
     """sparq_decode_step must leave exactly the state, and return exactly the outputs, of
@@ -437,12 +437,13 @@ def test_decode_step_on_a_full_sequence():
 # ------------------------------------------------------------------ digit-bucket plan (few heads, long cache)
 
 def test_split_plan_ragged_short_and_empty_sequences():
-    """S_max >= 8192 with few heads selects the digit-bucket kernels; sequences much shorter than the
+    """S_max >= 12288 with few heads selects the digit-bucket kernels; sequences much shorter than the
     slices (empty slices), k >= S, an empty sequence and every d_h go through them too."""
     for d_h, dtype, r in ((128, "f16", 16), (256, "bf16", 64), (64, "f16", 8)):
-        w = W.Workload("split_ragged", 4, 4, 2, d_h, 9000, r, 200, dtype, seed=40 + d_h)
-        seq = torch.tensor([9000, 37, 0, 1500], dtype=torch.int32)
-        b = Hn.build_cache(w, seq_lens=seq, S_max=9024, v_offset=True)
+        w = W.Workload("split_ragged", 4, 4, 2, d_h, 12400, r, 200, dtype, seed=40 + d_h)
+        seq = torch.tensor([12400, 37, 0, 1500], dtype=torch.int32)
+        b = Hn.build_cache(w, seq_lens=seq, S_max=12416, v_offset=True)
+        assert "digit-bucket" in B.sparq_decode_plan(b.cache.shape)
         q = W.draw_queries(w, b.K_src, seq, n=2, q_scale=0.02)
         for i in range(2):
             c = b.cache
@@ -453,7 +454,7 @@ def test_split_plan_ragged_short_and_empty_sequences():
         # the non-empty sequences against the oracle
         keep = [0, 1, 3]
         w3 = W.scaled(w, B=3)
-        sub = Hn.Built(w3, DecodeCache(3, w.H, w.H_kv, 9024, d_h, r, 200, w.torch_dtype), b.K_src[keep].contiguous(),
+        sub = Hn.Built(w3, DecodeCache(3, w.H, w.H_kv, 12416, d_h, r, 200, w.torch_dtype), b.K_src[keep].contiguous(),
                        b.V_src[keep].contiguous(), seq[keep], None)
         sub.cache.append(sub.K_src, sub.V_src, seq[keep].cuda())
         say(Hn.compare_decode(sub, q[0][keep].contiguous()))
@@ -463,25 +464,25 @@ def test_digit_bucket_plan_ties_identical_keys_and_ragged_k():
     """The digit-bucket plan's own degenerate cases: many duplicated keys (ties inside the threshold bucket are
     split by position), all keys identical (every key is a candidate: far more than the LDS holds, so they are
     ranked from the workspace), a per-sequence k, and the one-call step."""
-    w = W.Workload("bucket_ties", 2, 4, 2, 128, 12000, 16, 300, "f16", seed=44, recipe="gaussian", k_div=50)
-    assert "digit-bucket" in B.sparq_decode_plan(B.make_shape(w.B, w.H, w.H_kv, 12032, w.d_h, w.r, w.k, w.dtype_code))
+    w = W.Workload("bucket_ties", 2, 4, 2, 128, 12400, 16, 300, "f16", seed=44, recipe="gaussian", k_div=50)
+    assert "digit-bucket" in B.sparq_decode_plan(B.make_shape(w.B, w.H, w.H_kv, 12416, w.d_h, w.r, w.k, w.dtype_code))
     st = run(w, dup_rows=3000, n_q=2)
     say(st)
-    seq = torch.tensor([12000, 8700], dtype=torch.int32)
-    b = Hn.build_cache(w, seq_lens=seq, S_max=12032, dup_rows=2500, v_offset=True)
+    seq = torch.tensor([12400, 8700], dtype=torch.int32)
+    b = Hn.build_cache(w, seq_lens=seq, S_max=12416, dup_rows=2500, v_offset=True)
     b = Hn.Built(w, b.cache, b.K_src, b.V_src, b.seq_lens, W.k_per_seq(w, seq))
     q = W.draw_queries(w, b.K_src, b.seq_lens, q_scale=0.02)[0]
     say(Hn.compare_decode(b, q))
     kn, vn = W.draw_kv(W.scaled(w, seed=45), "cuda", n_rows=1, v_offset=True)
     out = b.cache.step(kn[:, :, 0].contiguous(), vn[:, :, 0].contiguous(), q, b.k_per_seq.cuda())
     torch.cuda.synchronize()
-    assert b.cache.seq_lens.cpu().tolist() == [12001, 8701] and b.cache.error_flags() == 0
+    assert b.cache.seq_lens.cpu().tolist() == [12401, 8701] and b.cache.error_flags() == 0
     assert torch.equal(out.view(torch.int16), b.cache.decode(q, b.k_per_seq.cuda()).view(torch.int16))
     # all keys identical: every score ties, the k lowest positions must be selected
     w1 = W.scaled(w, B=1, k_div=None)
     c = Hn.build_cache(w1)
     c.K_src[:] = c.K_src[:, :, :1]
-    c = Hn.Built(w1, DecodeCache(w1.B, w1.H, w1.H_kv, 12032, w1.d_h, w1.r, w1.k, w1.torch_dtype), c.K_src, c.V_src, c.seq_lens, None)
+    c = Hn.Built(w1, DecodeCache(w1.B, w1.H, w1.H_kv, 12416, w1.d_h, w1.r, w1.k, w1.torch_dtype), c.K_src, c.V_src, c.seq_lens, None)
     c.cache.append(c.K_src, c.V_src)
     q = W.draw_queries(w1, c.K_src, c.seq_lens)[0]
     out, alpha, idx, chan = c.cache.decode(q, aux=True)
@@ -503,7 +504,7 @@ def test_fixed_temperatures(flag):
     wg = W.Workload("tau_modes_gqa", 2, 8, 2, 128, 1100, 16, 96, "bf16", seed=61)
     run(wg, flags=flag, q_scale=0.02, v_offset=True)                                  # independent heads
     run(wg, flags=flag | B.SPARQ_FLAG_GQA_SHARED, q_scale=0.02, v_offset=True)        # the paper's group rule
-    ws = W.Workload("tau_modes_split", 1, 4, 4, 128, 9000, 32, 300, "f16", seed=62)   # digit-bucket plan
+    ws = W.Workload("tau_modes_split", 1, 4, 4, 128, 12400, 32, 300, "f16", seed=62)   # digit-bucket plan
     run(ws, flags=flag, q_scale=0.01, v_offset=True)
 
 
@@ -515,7 +516,7 @@ def test_local_window(l):
     st = run(w, local_window=l, q_scale=0.02, v_offset=True, seq_lens=seq)
     wg = W.Workload("window_gqa", 1, 8, 2, 128, 1100, 16, 64, "bf16", seed=64)
     run(wg, local_window=l, flags=B.SPARQ_FLAG_GQA_SHARED, q_scale=0.02, v_offset=True)
-    ws = W.Workload("window_split", 1, 4, 4, 128, 9000, 32, 64, "f16", seed=65)
+    ws = W.Workload("window_split", 1, 4, 4, 128, 12400, 32, 64, "f16", seed=65)
     run(ws, local_window=l, q_scale=0.01, v_offset=True)
 
 
@@ -817,7 +818,7 @@ SH, K1, TK = B.SPARQ_FLAG_GQA_SHARED, B.SPARQ_FLAG_SINGLE_K, B.SPARQ_FLAG_TILED_
 @pytest.mark.parametrize("name,kw,S_max,plan,flags,step", [
     ("bound_fused", dict(B=3, H=4, H_kv=4, d_h=128, S=1000, r=16, k=64, dtype="f16"), 8192, "sparq_decode_fused", 0, True),
     ("bound_fused_gqa_d256", dict(B=2, H=4, H_kv=2, d_h=256, S=1500, r=64, k=200, dtype="bf16"), 4096, "sparq_decode_fused", 0, False),
-    ("bound_bucket", dict(B=1, H=4, H_kv=2, d_h=128, S=9000, r=16, k=300, dtype="f16"), 20480, "digit-bucket", 0, True),
+    ("bound_bucket", dict(B=1, H=4, H_kv=2, d_h=128, S=12400, r=16, k=300, dtype="f16"), 20480, "digit-bucket", 0, True),
     ("bound_two_level", dict(B=5, H=32, H_kv=32, d_h=64, S=36001, r=8, k=100, dtype="f16"), 40960, "two-level", 0, True),
     ("bound_shared", dict(B=2, H=8, H_kv=2, d_h=128, S=3000, r=16, k=128, dtype="bf16"), 16384, "one workgroup per KV head", SH, True),
     ("bound_shared_bucket", dict(B=1, H=8, H_kv=2, d_h=128, S=9000, r=16, k=300, dtype="bf16"), 32768, "grouped-query rule on the digit-bucket", SH, True),
