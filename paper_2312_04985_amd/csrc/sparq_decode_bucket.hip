@@ -562,14 +562,30 @@ __global__ __launch_bounds__(NT) void bk_select_gather(const BucketArgs a) {
   };
 
   // ---- exact rank among the candidates: radix passes of 11, 11, 10 (the key) and 10, 10 bits (the position); stop
-  // as soon as the remaining bin is taken whole (with distinct keys: after the key bits at the latest) ----
+  // as soon as the remaining bin is taken whole (with distinct keys: after the key bits at the latest).  The keys of
+  // an ordinary bucket share their top 14 bits: then the passes take key bits 17..7 and 6..0 (one pass in practice:
+  // a few hundred candidates over 2048 bins) ----
   uint64_t mask = 0, thr = 0;
   if (need < C0) {
     int in_bin = C0;
-    for (int pass = 0; pass < 5 && need < in_bin; ++pass) {
-      const int shift = pass < 2 ? 41 - 11 * pass : 40 - 10 * pass;
-      const uint32_t dmask = pass < 2 ? 0x7ffu : 0x3ffu;
-      if (pass > 0) {
+    int first_pass = 0;
+    bool shared_top = false;
+    if (!GROUP) {
+      // An ordinary bucket away from the two ends of the exponent range fixes sign, exponent and five mantissa bits
+      // of its keys: take those 14 bits from any candidate instead of looking for them.
+      const uint32_t low = (uint32_t)ctl[1] >= 1024u ? (uint32_t)ctl[1] - 1024u : 1023u - (uint32_t)ctl[1];
+      if (low >= 1u && low <= 1021u) {
+        int t0;
+        thr = (candidate(0, t0) >> 38) << 38;
+        mask = (uint64_t)0x3fffu << 38;
+        first_pass = 1;
+        shared_top = true;
+      }
+    }
+    for (int pass = first_pass; pass < 5 && need < in_bin; ++pass) {
+      const int shift = pass == 0 ? 41 : (pass == 1 ? (shared_top ? 27 : 30) : 40 - 10 * pass);
+      const uint32_t dmask = pass < 2 ? 0x7ffu : (pass == 2 && shared_top ? 0x7fu : 0x3ffu);
+      if (pass > first_pass) {
         for (int i = tid; i < kRadixBins; i += NT) hist[i] = 0u;
         __syncthreads();
       }
