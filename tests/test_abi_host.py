@@ -69,6 +69,19 @@ def test_a_bound_on_the_lengths_sizes_plan_and_workspace():
     assert "one workgroup per head" in B.sparq_decode_plan(shape(S_max=131072, S_bound=4096, **few))
 
 
+def test_plan_choice_between_the_bucket_plan_and_one_workgroup_per_unit():
+    """Few units with long caches go to the digit-bucket plan only where it was measured faster (or where one
+    workgroup cannot hold the keys)."""
+    plan = lambda **kw: B.sparq_decode_plan(shape(H=32, H_kv=32, r=32, k=512, **kw))
+    one, bucket = "one workgroup per head", "digit-bucket"
+    assert one in plan(B=1, S_max=8192) and one in plan(B=4, S_max=8192) and one in plan(B=2, S_max=12224)
+    assert bucket in plan(B=1, S_max=12288) and bucket in plan(B=2, S_max=12288) and one in plan(B=3, S_max=12288)
+    assert bucket in plan(B=3, S_max=16384) and one in plan(B=4, S_max=16384)
+    assert bucket in plan(B=3, S_max=32768) and one in plan(B=4, S_max=32768) and one in plan(B=16, S_max=32768)
+    assert bucket in plan(B=4, S_max=65536)                      # beyond one workgroup's LDS: up to 128 units
+    assert "two-level" in plan(B=5, S_max=65536)
+
+
 def test_workspace_bytes_and_shape_validation():
     need = B.sparq_workspace_bytes(shape())
     assert need >= 256 + 2 * 4 * (128 + 2) * 4
