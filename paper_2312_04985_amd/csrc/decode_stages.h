@@ -389,9 +389,9 @@ __device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wsum, 
 
 // Ordered compaction of the selected positions into list[0..kq) (ascending) and
 // alpha = (sum over the selected of exp((d - dmax)/tau)) / (sum over all): Step 3's weight.
-// A lane owns m = ceil(chunks / NT) <= 4 consecutive chunks per sweep, so lane order is position order and one
-// workgroup scan of the packed (above-threshold, equal-to-threshold) counts orders a whole sweep of 8 m NT
-// positions: one barrier for lengths up to 16 384, whatever the length is a multiple of.  (Sweeps of NT chunks,
+// A lane owns up to 4 consecutive chunks per sweep (the chunks of a sweep are dealt out evenly), so lane order is
+// position order and one workgroup scan of the packed (above-threshold, equal-to-threshold) counts orders a whole
+// sweep of up to 32 NT positions: one barrier for lengths up to 16 384, whatever the length is a multiple of.  (Sweeps of NT chunks,
 // one per lane, needed ceil(S / 4096) scans, and a last sweep of a few chunks still cost 0.5 us of one wave's
 // dependent arithmetic: 3-4 us per launch at a length just above a multiple of 4096 with 2048 heads.)
 // Before the scan a lane reads its keys and sums the softmax weights: of all keys, of the keys above the
@@ -415,18 +415,20 @@ __device__ __forceinline__ float compact_selected(const uint32_t* keys, uint32_t
                                                   int lane, int wave, uint32_t* key_out = nullptr, int pos_base = 0,
                                                   float* sums_out = nullptr) {
   const int n_chunks = (S + 7) >> 3;
-  int m = (n_chunks + NT - 1) / NT;
-  m = m > 4 ? 4 : m;
   float zsum = 0.0f, asum = 0.0f, esum = 0.0f;
   uint32_t run_gt = 0, run_eq = 0;
   int sweep = 0;
-  for (int c0 = 0; c0 < n_chunks; c0 += NT * m, ++sweep) {
-    const int cb = c0 + tid * m;                 // the lane's first chunk of this sweep
+  for (int c0 = 0; c0 < n_chunks; c0 += 4 * NT, ++sweep) {
+    // the chunks of this sweep dealt out evenly, in order: the first `rem` lanes take one more than the others
+    const int n_here = n_chunks - c0 < 4 * NT ? n_chunks - c0 : 4 * NT;
+    const int per = n_here / NT, rem = n_here - per * NT;
+    const int cb = c0 + tid * per + (tid < rem ? tid : rem);   // the lane's first chunk of this sweep
+    const int mine = per + (tid < rem ? 1 : 0);
     uint32_t gt_bits = 0, eq_bits = 0;           // bit 8 i + e: key e of the lane's i-th chunk
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int c = cb + i;
-      if (i < m && c < n_chunks) {
+      if (i < mine) {
         const uint4* src = reinterpret_cast<const uint4*>(keys + c * 8);
         const uint4 lo = src[0], hi = src[1];
         const uint32_t kx[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
